@@ -1,0 +1,559 @@
+// Host side of the C ABI declared in include/hgemm.h: plan construction (spec
+// parsing, dispatch table lookup, heuristics), launch, and helpers.
+#include "../../include/hgemm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "hgemm_aux.hpp"
+#include "hgemm_mfma.hpp"
+
+namespace hgemm {
+
+// ---------------------------------------------------------------------------
+// Kernel registry: every compiled MFMA specialisation.
+// ---------------------------------------------------------------------------
+struct MfmaEntry {
+    int bm, bn, bk, wm, wn, st;
+    int threads, lds_bytes;
+    void (*plain)(GemmArgs);
+    void (*splitk)(GemmArgs);
+};
+
+template <class C> static MfmaEntry make_entry()
+{
+    return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::THREADS, C::LDS_BYTES,
+                     mfma_gemm_kernel<C, false>, mfma_gemm_kernel<C, true>};
+}
+
+#define HGEMM_MFMA_CONFIGS(X)                                                                    \
+    X(256, 256, 64, 2, 2, 2)                                                                     \
+    X(256, 256, 32, 2, 2, 3)                                                                     \
+    X(256, 256, 32, 2, 2, 4)                                                                     \
+    X(256, 128, 64, 2, 2, 2)                                                                     \
+    X(256, 128, 64, 2, 2, 3)                                                                     \
+    X(128, 256, 64, 2, 2, 2)                                                                     \
+    X(128, 256, 64, 2, 2, 3)                                                                     \
+    X(128, 128, 64, 2, 2, 2)                                                                     \
+    X(128, 128, 64, 2, 2, 4)                                                                     \
+    X(128, 128, 32, 2, 2, 4)                                                                     \
+    X(128, 64, 64, 2, 2, 4)                                                                      \
+    X(64, 128, 64, 2, 2, 4)                                                                      \
+    X(64, 64, 64, 2, 2, 4)                                                                       \
+    X(64, 256, 64, 1, 4, 3)                                                                      \
+    X(32, 256, 64, 1, 4, 4)                                                                      \
+    X(32, 128, 64, 1, 4, 4)                                                                      \
+    X(32, 128, 128, 1, 4, 4)                                                                     \
+    X(256, 256, 64, 2, 4, 2)
+
+static const std::vector<MfmaEntry>& registry()
+{
+    static const std::vector<MfmaEntry> r = {
+#define X(bm, bn, bk, wm, wn, st) make_entry<MfmaCfg<bm, bn, bk, wm, wn, st>>(),
+        HGEMM_MFMA_CONFIGS(X)
+#undef X
+    };
+    return r;
+}
+
+enum Family { FAM_GENERIC = 0, FAM_MFMA = 1 };
+
+struct Spec {
+    Family fam = FAM_GENERIC;
+    int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0, st = 0;
+    int sk = 1;     // split-K factor
+    int gm = 8;     // tile-order group height; 0 = row-major
+};
+
+static std::string spec_to_string(const Spec& s)
+{
+    char buf[160];
+    if (s.fam == FAM_GENERIC) return "generic";
+    snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,sk=%d,gm=%d", s.bm, s.bn, s.bk, s.wm, s.wn,
+             s.st, s.sk, s.gm);
+    return buf;
+}
+
+static bool parse_spec(const char* text, Spec* out)
+{
+    if (!text) return false;
+    std::string s(text);
+    size_t pos = s.find(',');
+    std::string fam = s.substr(0, pos);
+    Spec sp;
+    if (fam == "generic") {
+        sp.fam = FAM_GENERIC;
+    } else if (fam == "mfma") {
+        sp.fam = FAM_MFMA;
+    } else {
+        return false;
+    }
+    while (pos != std::string::npos) {
+        size_t next = s.find(',', pos + 1);
+        std::string kv = s.substr(pos + 1, next == std::string::npos ? std::string::npos : next - pos - 1);
+        pos = next;
+        size_t eq = kv.find('=');
+        if (eq == std::string::npos || eq == 0 || eq + 1 >= kv.size()) return false;
+        std::string key = kv.substr(0, eq);
+        char* end = nullptr;
+        long v = strtol(kv.c_str() + eq + 1, &end, 10);
+        if (*end != '\0' || v < 0 || v > (1 << 20)) return false;
+        if (key == "bm") sp.bm = (int)v;
+        else if (key == "bn") sp.bn = (int)v;
+        else if (key == "bk") sp.bk = (int)v;
+        else if (key == "wm") sp.wm = (int)v;
+        else if (key == "wn") sp.wn = (int)v;
+        else if (key == "st") sp.st = (int)v;
+        else if (key == "sk") sp.sk = (int)v;
+        else if (key == "gm") sp.gm = (int)v;
+        else return false;
+    }
+    if (sp.sk < 1) return false;
+    *out = sp;
+    return true;
+}
+
+static const MfmaEntry* find_entry(const Spec& s)
+{
+    for (const MfmaEntry& e : registry())
+        if (e.bm == s.bm && e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.st == s.st) return &e;
+    return nullptr;
+}
+
+}  // namespace hgemm
+
+using namespace hgemm;
+
+struct hgemm_plan_s {
+    int64_t M, N, K;
+    hgemm_layouts_t lay;        // with packed leading dimensions resolved
+    Spec spec;
+    const MfmaEntry* entry;     // null for the generic family
+    GemmArgs args;              // pointers filled in at run time
+    void* workspace;
+    size_t workspace_bytes;
+    int device;
+};
+
+namespace {
+
+bool fast_path_ok(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l)
+{
+    if (l.b != HGEMM_ROW_MAJOR) return false;
+    if (N % 8 || K % 8 || l.lda % 8 || l.ldb % 8 || l.ldc % 8) return false;
+    // buffer offsets are 32-bit and bit 31 marks "out of range": keep every operand, including
+    // the rows a padded tile may address, below 2 GiB
+    const int64_t lim = (int64_t)1 << 31;
+    if ((M + 512) * l.lda * 2 >= lim || (K + 512) * l.ldb * 2 >= lim || M * l.ldc * 2 >= ((int64_t)1 << 33)) return false;
+    if (M >= (1 << 24) || N >= (1 << 24) || K >= (1 << 24)) return false;
+    return true;
+}
+
+// Rules used when the measured table has no row for the shape.  They follow the trends of
+// Section 6 (tile height/width grow with M/N; more stages for long K) with MI355X numbers:
+// 256 CUs want >= 256 workgroups, so small problems take smaller tiles or split K.
+Spec heuristic(int64_t M, int64_t N, int64_t K)
+{
+    Spec s;
+    s.fam = FAM_MFMA;
+    s.gm = 8;
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    const int CUS = 256;
+    if (M <= 32) {
+        s.bm = 32; s.bn = 128; s.bk = 64; s.wm = 1; s.wn = 4; s.st = 4;
+    } else if (M <= 64) {
+        s.bm = 64; s.bn = 128; s.bk = 64; s.wm = 2; s.wn = 2; s.st = 4;
+    } else if (tiles(256, 256) >= CUS) {
+        s.bm = 256; s.bn = 256; s.bk = 64; s.wm = 2; s.wn = 2; s.st = 2;
+    } else if (tiles(128, 128) >= CUS || M * N >= (int64_t)2048 * 2048) {
+        s.bm = 128; s.bn = 128; s.bk = 64; s.wm = 2; s.wn = 2; s.st = 4;
+    } else {
+        s.bm = 64; s.bn = 64; s.bk = 64; s.wm = 2; s.wn = 2; s.st = 4;
+        if (M >= 128 && N >= 128 && tiles(128, 128) * 4 >= CUS) { s.bm = 128; s.bn = 128; }
+    }
+    // split K when the grid leaves most CUs idle and K is long enough to share
+    const int64_t t = tiles(s.bm, s.bn);
+    s.sk = 1;
+    if (t < CUS && K >= 1024) {
+        int64_t want = (2 * CUS + t - 1) / t;                 // aim at about two workgroups per CU
+        int64_t max_by_k = K / (4 * s.bk);                    // at least four K-tiles per split
+        s.sk = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_k), 64));
+    }
+    return s;
+}
+
+#include "dispatch_table.inc"
+
+bool table_lookup(int64_t M, int64_t N, int64_t K, Spec* out)
+{
+    for (size_t i = 0; i < sizeof(kDispatchTable) / sizeof(kDispatchTable[0]); ++i) {
+        const DispatchRow& r = kDispatchTable[i];
+        if (r.m == M && r.n == N && r.k == K) return r.spec[0] != '\0' && parse_spec(r.spec, out);
+    }
+    return false;
+}
+
+hgemm_status_t finish_plan(hgemm_plan_s* p)
+{
+    const int64_t M = p->M, N = p->N, K = p->K;
+    Spec& s = p->spec;
+    p->entry = nullptr;
+    p->workspace = nullptr;
+    p->workspace_bytes = 0;
+    memset(&p->args, 0, sizeof p->args);
+    if (s.fam == FAM_GENERIC) return HGEMM_OK;
+    const MfmaEntry* e = find_entry(s);
+    if (!e) return HGEMM_ERR_UNSUPPORTED;
+    if (!fast_path_ok(M, N, K, p->lay)) return HGEMM_ERR_UNSUPPORTED;
+    p->entry = e;
+    // dynamic LDS beyond 64 KiB has to be requested per kernel function
+    if (hipFuncSetAttribute((const void*)e->plain, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->splitk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return HGEMM_ERR_LAUNCH;
+    }
+    GemmArgs& a = p->args;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.lda = (int)p->lay.lda; a.ldb = (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
+    a.tiles_m = (int)((M + e->bm - 1) / e->bm);
+    a.tiles_n = (int)((N + e->bn - 1) / e->bn);
+    if ((int64_t)a.tiles_m * a.tiles_n >= ((int64_t)1 << 31)) return HGEMM_ERR_UNSUPPORTED;
+    a.swizzle = s.gm;
+    // split K into ranges that are multiples of BK; drop splits that would be empty
+    int64_t ktiles = (K + e->bk - 1) / e->bk;
+    int64_t sk = std::min<int64_t>(s.sk, std::max<int64_t>(ktiles, 1));
+    int64_t per = (ktiles + sk - 1) / sk;
+    sk = (ktiles + per - 1) / std::max<int64_t>(per, 1);
+    if (sk < 1) sk = 1;
+    if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
+    s.sk = (int)sk;
+    a.splits = (int)sk;
+    a.k_per_split = (int)(per * e->bk);
+    if (sk > 1) {
+        p->workspace_bytes = (size_t)sk * (size_t)M * (size_t)N * sizeof(float);
+        if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            p->workspace = nullptr;
+            return HGEMM_ERR_ALLOC;
+        }
+        a.partial = (float*)p->workspace;
+    }
+    return HGEMM_OK;
+}
+
+hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
+                         const char* spec_text)
+{
+    if (!out) return HGEMM_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0) return HGEMM_ERR_INVALID_ARG;
+    hgemm_layouts_t l;
+    if (layouts) {
+        l = *layouts;
+    } else {
+        l.a = l.b = l.c = HGEMM_ROW_MAJOR;
+        l.lda = l.ldb = l.ldc = 0;
+    }
+    if ((l.a != HGEMM_ROW_MAJOR && l.a != HGEMM_COL_MAJOR) || (l.b != HGEMM_ROW_MAJOR && l.b != HGEMM_COL_MAJOR) ||
+        (l.c != HGEMM_ROW_MAJOR && l.c != HGEMM_COL_MAJOR))
+        return HGEMM_ERR_INVALID_ARG;
+    if (l.a != HGEMM_ROW_MAJOR || l.c != HGEMM_ROW_MAJOR) return HGEMM_ERR_UNSUPPORTED;
+    if (l.lda < 0 || l.ldb < 0 || l.ldc < 0) return HGEMM_ERR_INVALID_ARG;
+    if (l.lda == 0) l.lda = K;
+    if (l.ldb == 0) l.ldb = (l.b == HGEMM_ROW_MAJOR) ? N : K;
+    if (l.ldc == 0) l.ldc = N;
+    if (l.lda < K || l.ldc < N || l.ldb < ((l.b == HGEMM_ROW_MAJOR) ? N : K)) return HGEMM_ERR_INVALID_ARG;
+
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return HGEMM_ERR_ARCH;
+
+    hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s;
+    if (!p) return HGEMM_ERR_ALLOC;
+    p->M = M; p->N = N; p->K = K; p->lay = l; p->device = dev;
+
+    hgemm_status_t st;
+    if (spec_text) {
+        if (!parse_spec(spec_text, &p->spec)) { delete p; return HGEMM_ERR_INVALID_ARG; }
+        st = finish_plan(p);
+    } else {
+        bool fast = fast_path_ok(M, N, K, l) && M > 0 && N > 0 && K > 0;
+        if (!fast) {
+            p->spec = Spec();
+            st = finish_plan(p);
+        } else {
+            if (!table_lookup(M, N, K, &p->spec) || !(l.lda == K && l.ldb == N && l.ldc == N)) p->spec = heuristic(M, N, K);
+            st = finish_plan(p);
+            if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
+                p->spec = heuristic(M, N, K);
+                st = finish_plan(p);
+            }
+        }
+    }
+    if (st != HGEMM_OK) { delete p; return st; }
+    *out = p;
+    return HGEMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+hgemm_status_t hgemm_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts)
+{
+    return make_plan(out, M, N, K, layouts, nullptr);
+}
+
+hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
+                                   const char* spec)
+{
+    if (!spec) return HGEMM_ERR_INVALID_ARG;
+    return make_plan(out, M, N, K, layouts, spec);
+}
+
+hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* C, void* hip_stream)
+{
+    if (!plan) return HGEMM_ERR_INVALID_ARG;
+    const int64_t M = plan->M, N = plan->N, K = plan->K;
+    if (M == 0 || N == 0) return HGEMM_OK;
+    if (!C) return HGEMM_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (K == 0) {
+        const int64_t total = M * N;
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 4096);
+        hipLaunchKernelGGL(zero_c_kernel, dim3(blocks), dim3(256), 0, stream, (_Float16*)C, M, N, plan->lay.ldc);
+        return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
+    }
+    if (!A || !B) return HGEMM_ERR_INVALID_ARG;
+
+    const bool aligned = ((((uintptr_t)A) | ((uintptr_t)B) | ((uintptr_t)C)) & 15) == 0;
+    if (plan->spec.fam == FAM_GENERIC || !aligned) {
+        if (N > (int64_t)64 * 0x7fffffff || (M + 3) / 4 > 65535) {
+            // grid.y limit: fold rows into several launches
+            for (int64_t mb = 0; mb < M; mb += 4 * 65535) {
+                const int64_t rows = std::min<int64_t>(M - mb, 4 * 65535);
+                hipLaunchKernelGGL(generic_gemm_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((rows + 3) / 4)), dim3(256), 0,
+                                   stream, (const _Float16*)A + mb * plan->lay.lda, (const _Float16*)B,
+                                   (_Float16*)C + mb * plan->lay.ldc, rows, N, K, plan->lay.lda, plan->lay.ldb, plan->lay.ldc,
+                                   plan->lay.b == HGEMM_COL_MAJOR ? 1 : 0);
+            }
+        } else {
+            hipLaunchKernelGGL(generic_gemm_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((M + 3) / 4)), dim3(256), 0, stream,
+                               (const _Float16*)A, (const _Float16*)B, (_Float16*)C, M, N, K, plan->lay.lda, plan->lay.ldb,
+                               plan->lay.ldc, plan->lay.b == HGEMM_COL_MAJOR ? 1 : 0);
+        }
+        return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
+    }
+
+    GemmArgs a = plan->args;
+    a.A = (const _Float16*)A;
+    a.B = (const _Float16*)B;
+    a.C = (_Float16*)C;
+    const MfmaEntry* e = plan->entry;
+    const unsigned wgs = (unsigned)(a.tiles_m * a.tiles_n);
+    if (a.splits > 1) {
+        hipLaunchKernelGGL(e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes, stream, a);
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        const int64_t quads = M * (N / 4);
+        const int blocks = (int)std::min<int64_t>((quads + 255) / 256, 2048);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float*)plan->workspace, (_Float16*)C,
+                           (int)M, (int)N, (int)plan->lay.ldc, a.splits);
+    } else {
+        hipLaunchKernelGGL(e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
+    }
+    return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
+}
+
+hgemm_status_t hgemm_destroy(hgemm_plan_t plan)
+{
+    if (!plan) return HGEMM_OK;
+    if (plan->workspace) {
+        if (hipFree(plan->workspace) != hipSuccess) (void)hipGetLastError();
+    }
+    delete plan;
+    return HGEMM_OK;
+}
+
+const char* hgemm_status_string(hgemm_status_t status)
+{
+    switch (status) {
+        case HGEMM_OK: return "ok";
+        case HGEMM_ERR_INVALID_ARG: return "invalid argument";
+        case HGEMM_ERR_UNSUPPORTED: return "unsupported layout, alignment or specialisation";
+        case HGEMM_ERR_ALLOC: return "allocation failed";
+        case HGEMM_ERR_LAUNCH: return "kernel launch failed";
+        case HGEMM_ERR_ARCH: return "device is not gfx950";
+    }
+    return "unknown status";
+}
+
+hgemm_status_t hgemm_plan_describe(hgemm_plan_t plan, char* buf, size_t n)
+{
+    if (!plan || !buf || n == 0) return HGEMM_ERR_INVALID_ARG;
+    const std::string s = spec_to_string(plan->spec);
+    if (s.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
+    memcpy(buf, s.c_str(), s.size() + 1);
+    return HGEMM_OK;
+}
+
+size_t hgemm_plan_workspace_bytes(hgemm_plan_t plan) { return plan ? plan->workspace_bytes : 0; }
+
+hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, int64_t* lds_bytes, int64_t* threads)
+{
+    if (!plan) return HGEMM_ERR_INVALID_ARG;
+    int64_t wg, lds, th;
+    if (plan->entry) {
+        wg = (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
+        lds = plan->entry->lds_bytes;
+        th = plan->entry->threads;
+    } else {
+        wg = ((plan->N + 63) / 64) * ((plan->M + 3) / 4);
+        lds = 0;
+        th = 256;
+    }
+    if (workgroups) *workgroups = wg;
+    if (lds_bytes) *lds_bytes = lds;
+    if (threads) *threads = th;
+    return HGEMM_OK;
+}
+
+const char* hgemm_spec_help(void)
+{
+    static std::string text;
+    if (text.empty()) {
+        std::string t =
+            "generic\n"
+            "    one thread per element, any shape, alignment and layout\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,sk=SPLITS][,gm=GROUP]\n"
+            "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
+            "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major)\n"
+            "    compiled (bm,bn,bk,wm,wn,st):";
+        for (const MfmaEntry& e : registry()) {
+            char b[64];
+            snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st);
+            t += b;
+        }
+        t += "\n";
+        text = t;
+    }
+    return text.c_str();
+}
+
+hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, char* buf, size_t n)
+{
+    if (!buf || n == 0 || M < 0 || N < 0 || K < 0) return HGEMM_ERR_INVALID_ARG;
+    hgemm_layouts_t l;
+    if (layouts) l = *layouts; else { l.a = l.b = l.c = HGEMM_ROW_MAJOR; l.lda = l.ldb = l.ldc = 0; }
+    if (l.lda == 0) l.lda = K;
+    if (l.ldb == 0) l.ldb = (l.b == HGEMM_ROW_MAJOR) ? N : K;
+    if (l.ldc == 0) l.ldc = N;
+    std::string out;
+    if (!fast_path_ok(M, N, K, l) || M == 0 || N == 0 || K == 0) {
+        out = "generic\n";
+    } else {
+        const int64_t CUS = 256;
+        for (const MfmaEntry& e : registry()) {
+            // tiles far taller/wider than the problem only waste matrix-core work
+            if (e.bm >= 2 * M && e.bm > 32) continue;
+            if (e.bn >= 2 * N && e.bn > 64) continue;
+            const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
+            const int64_t ktiles = (K + e.bk - 1) / e.bk;
+            std::vector<int> sks = {1};
+            if (t < 2 * CUS) {
+                for (int sk : {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64}) {
+                    if (ktiles / sk < 2) break;
+                    if (t * sk > 8 * CUS) break;
+                    sks.push_back(sk);
+                }
+            }
+            for (int sk : sks) {
+                for (int gm : {8, 0, 4, 16}) {
+                    if (gm != 8 && (t < 2 * CUS)) continue;      // order matters only when tiles outnumber CUs
+                    Spec s;
+                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.sk = sk; s.gm = gm;
+                    out += spec_to_string(s);
+                    out += "\n";
+                }
+            }
+        }
+    }
+    if (out.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
+    memcpy(buf, out.c_str(), out.size() + 1);
+    return HGEMM_OK;
+}
+
+int64_t hgemm_tiles(int64_t dim, int64_t tile) { return (dim < 0 || tile <= 0) ? -1 : (dim + tile - 1) / tile; }
+int64_t hgemm_padded(int64_t dim, int64_t tile) { return (dim < 0 || tile <= 0) ? -1 : ((dim + tile - 1) / tile) * tile; }
+
+int64_t hgemm_tile_of_workgroup(int64_t wg, int64_t tiles_m, int64_t tiles_n, int64_t swizzle)
+{
+    if (tiles_m <= 0 || tiles_n <= 0 || wg < 0 || wg >= tiles_m * tiles_n || swizzle < 0) return -1;
+    return tile_of_workgroup(wg, tiles_m, tiles_n, swizzle);
+}
+
+hgemm_status_t hgemm_calibrate_mfma(int64_t iters, void* hip_stream, double* ms, double* flop)
+{
+    if (!ms || !flop || iters <= 0 || iters > (1 << 24)) return HGEMM_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
+    float* out = nullptr;
+    if (hipMalloc(&out, 4) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ALLOC; }
+    hipEvent_t e0, e1;
+    hipEventCreate(&e0);
+    hipEventCreate(&e1);
+    const int blocks = prop.multiProcessorCount * 2;
+    hipLaunchKernelGGL(calib_mfma_kernel, dim3(blocks), dim3(256), 0, stream, out, (int)iters);   // warm-up
+    hipEventRecord(e0, stream);
+    hipLaunchKernelGGL(calib_mfma_kernel, dim3(blocks), dim3(256), 0, stream, out, (int)iters);
+    hipEventRecord(e1, stream);
+    hipError_t err = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&t, e0, e1);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    hipFree(out);
+    if (err != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_LAUNCH; }
+    *ms = t;
+    *flop = (double)blocks * 4.0 * (double)iters * 4.0 * 32768.0;    // 4 waves x 4 MFMAs of 32*32*16*2 flop
+    return HGEMM_OK;
+}
+
+hgemm_status_t hgemm_calibrate_hbm_read(const void* src, size_t bytes, void* hip_stream, double* ms)
+{
+    if (!src || !ms || bytes < 16 || (((uintptr_t)src) & 15)) return HGEMM_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
+    uint32_t* out = nullptr;
+    if (hipMalloc(&out, 4) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ALLOC; }
+    hipEvent_t e0, e1;
+    hipEventCreate(&e0);
+    hipEventCreate(&e1);
+    const int blocks = prop.multiProcessorCount * 8;
+    hipEventRecord(e0, stream);
+    hipLaunchKernelGGL(calib_read_kernel, dim3(blocks), dim3(256), 0, stream, (const uint4*)src, bytes / 16, out);
+    hipEventRecord(e1, stream);
+    hipError_t err = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&t, e0, e1);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    hipFree(out);
+    if (err != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_LAUNCH; }
+    *ms = t;
+    return HGEMM_OK;
+}
+
+}  // extern "C"

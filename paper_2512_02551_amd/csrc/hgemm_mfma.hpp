@@ -1,0 +1,342 @@
+// Pipelined MFMA HGEMM kernel for gfx950 (CDNA4), NN layout.
+//
+// Structure follows the three phases the paper describes for a tiled HGEMM
+// (Section 2.1): (1) one BM x BN tile of C per workgroup, cut into 32x32
+// matrix-core tiles per wavefront; (2) a main loop that stages BM x BK of A
+// and BK x BN of B from global memory into LDS, reads fragments from LDS into
+// registers and accumulates in registers over all of K; (3) an epilogue that
+// rounds and stores.  The techniques of Section 5.3 appear in their CDNA4
+// form:
+//   * asynchronous 128-bit global->shared copies   -> buffer_load_dwordx4 ... lds
+//     (data goes HBM -> LDS without passing through VGPRs);
+//   * multi-stage pipelining (n_stage)             -> STAGES LDS buffers, loads
+//     issued STAGES-1 K-tiles ahead of use;
+//   * shared-memory swizzle against bank conflicts -> XOR of the 16-byte chunk
+//     index with a function of the row, applied on the global side (the LDS
+//     side of a direct load is always linear in the lane id);
+//   * double-buffered register fragments (5.3.1)   -> frag[2], next k-step read
+//     from LDS while the current one feeds the matrix cores, also across the
+//     K-tile boundary;
+//   * register accumulation                        -> fp32 accumulators live in
+//     (Acc)VGPRs for the whole K range;
+//   * zero padding to non-divisor tiles (5.2)      -> out-of-range rows/columns
+//     are read as zeros by the buffer bounds check or a per-lane predicate and
+//     are never stored;
+//   * block swizzle (5.3, 6.3)                     -> XCD-aware tile order.
+//
+// Row-major B is the hard operand: the matrix core wants, per lane, 8
+// consecutive k for one column n, while memory has n contiguous.  The LDS
+// transposing read ds_read_b64_tr_b16 does the turn: within each group of 16
+// lanes, lane s supplies the address of 4 consecutive n at row k0 + s/4,
+// column 4*(s%4); lane i receives the four k-values of column i.
+//
+// The roles of the two MFMA operands are swapped (the instruction computes the
+// 32x32 tile of C^T): the "A" operand carries B-fragments, the "B" operand
+// A-fragments.  A lane then owns 4 consecutive columns of one row of C, which
+// is the contiguous direction of row-major C.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hgemm {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+#define HGEMM_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+
+struct GemmArgs {
+    const _Float16* A;
+    const _Float16* B;
+    _Float16* C;
+    float* partial;      // split-K: [S][M][N] fp32, else unused
+    int M, N, K;
+    int lda, ldb, ldc;   // elements
+    int tiles_m, tiles_n;
+    int swizzle;         // group height in tiles for the tile order; 0 = row-major
+    int k_per_split;     // K range of one split, a multiple of BK (== K rounded up when not split)
+    int splits;
+};
+
+// ---------------------------------------------------------------------------
+// Tile order.  Hardware deals workgroup ids round-robin to the 8 XCDs, each
+// with a private L2.  Step 1 renumbers ids so that, inside every run of 256
+// consecutive ids (one workgroup per CU), each XCD owns 32 consecutive logical
+// ids.  Step 2 walks the tile grid in bands of `group` tile-rows, column by
+// column inside a band, so 32 consecutive logical ids form a compact
+// group x (32/group) block that shares A rows and B columns in one L2.
+// ---------------------------------------------------------------------------
+__host__ __device__ inline int64_t tile_of_workgroup(int64_t wg, int64_t tiles_m, int64_t tiles_n, int64_t group)
+{
+    const int64_t total = tiles_m * tiles_n;
+    const int64_t XCDS = 8, WAVE = 256;
+    int64_t logical = wg;
+    if (group > 0) {
+        const int64_t base = (wg / WAVE) * WAVE;
+        const int64_t span = (total - base < WAVE) ? (total - base) : WAVE;   // ids in this run
+        const int64_t within = wg - base;
+        const int64_t xcd = within % XCDS, seq = within / XCDS;
+        const int64_t q = span / XCDS, r = span % XCDS;
+        const int64_t start = xcd * q + (xcd < r ? xcd : r);                    // first logical id of this XCD
+        logical = base + start + seq;
+        // band walk
+        const int64_t band_sz = group * tiles_n;
+        const int64_t band = logical / band_sz;
+        const int64_t first_m = band * group;
+        const int64_t rows = (tiles_m - first_m < group) ? (tiles_m - first_m) : group;
+        const int64_t in_band = logical - band * band_sz;
+        const int64_t tm = first_m + in_band % rows;
+        const int64_t tn = in_band / rows;
+        return tm * tiles_n + tn;
+    }
+    return logical;
+}
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_>
+struct MfmaCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int NWAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = 64 * NWAVES;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;       // wave tile
+    static constexpr int TM = WTM / 32, TN = WTN / 32;                 // 32x32 MFMA tiles per wave
+    static constexpr int KS = BK / 16;                                 // k-steps per K-tile
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    // one wave-wide direct load moves 64 lanes x 16 B = 1 KiB, linear in LDS
+    static constexpr int A_LOADS = A_BYTES / 1024 / NWAVES;            // per wave per K-tile
+    static constexpr int B_LOADS = B_BYTES / 1024 / NWAVES;
+    static constexpr int LOADS = A_LOADS + B_LOADS;
+    static constexpr int A_CPR = BK / 8;                               // 16-byte chunks per A row
+    static constexpr int A_RPI = 64 / A_CPR;                           // A rows per wave-load
+    static constexpr int A_RP = 256 / (BK * 2);                        // A rows per 256 B of LDS
+    static constexpr int B_CPR = BN / 8;
+    static constexpr int B_RPI = 64 / B_CPR;                           // B rows per wave-load (may be 0 if BN > 512)
+    static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
+    static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
+    static_assert(KS % 2 == 0, "fragment ping-pong needs an even number of k-steps");
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into wave loads");
+    static_assert(BN >= 64 && BN <= 512, "BN");
+    static_assert((NWAVES * A_RPI) % 16 == 0, "A swizzle must be periodic in the rows one round of loads covers");
+    static_assert((NWAVES * B_RPI) % 4 == 0, "B swizzle periodicity");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    static_assert(LOADS * (STAGES - 1) <= 63, "vmcnt is 6 bits");
+};
+
+// XOR applied to the 16-byte chunk index of an A row (rows of BK halves).
+template <class C> __device__ inline int swz_a(int row) { return (row / C::A_RP) % C::A_CPR; }
+// XOR applied to the chunk index of a B row (rows of BN halves): the four rows
+// k..k+3 one transposing read touches must land in four different 64-byte
+// quarters of the 256-byte bank window.
+template <class C> __device__ inline int swz_b(int k)
+{
+    if (C::BN >= 128) return (k & 3) << 2;
+    return ((k >> 1) & 1) << 2;      // BN == 64: a row is 128 B, rows k and k+1 already differ
+}
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor (gfx9 layout): 48-bit base, stride 0, byte count, data-format word.
+// A load whose byte offset is >= `bytes` returns zero instead of touching memory.
+__device__ inline int4v make_rsrc(const void* base, unsigned bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    int4v r;
+    r[0] = (int)(uint32_t)a;
+    r[1] = (int)(uint32_t)((a >> 32) & 0xffffu);
+    r[2] = (int)bytes;
+    r[3] = 0x00020000;
+    return r;
+}
+
+// One wave-wide asynchronous copy HBM -> LDS: lane i moves 16 bytes from base + voff(i) to
+// LDS address lds_addr + 16*i (M0 carries the wave-uniform LDS base).  Issued through inline
+// assembly on purpose: the completion of these copies is tracked by hand with vmcnt (see
+// wait_vmcnt), and the compiler must not serialise every later LDS read behind them.
+__device__ inline void dma16(int4v rsrc, unsigned lds_addr, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+__device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)HGEMM_LDS(p); }
+
+template <int N> __device__ inline void wait_vmcnt()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt range");
+    // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]; leave exp/lgkm at "no wait"
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <class C, bool SPLITK>
+__global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+    const int tile = (int)tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, g.swizzle);
+    const int m0 = (tile / g.tiles_n) * C::BM;
+    const int n0 = (tile % g.tiles_n) * C::BN;
+    const int split = SPLITK ? blockIdx.y : 0;
+    const int k_begin = split * g.k_per_split;
+    const int k_end = min(g.K, k_begin + g.k_per_split);
+    const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
+
+    const unsigned OOB = 0x80000000u;        // beyond every num_records the host admits
+    const int4v rsrcA = make_rsrc(g.A, (unsigned)min((long long)g.M * g.lda * 2, 0x7fffffffLL));
+    const int4v rsrcB = make_rsrc(g.B, (unsigned)min((long long)k_end * g.ldb * 2, 0x7fffffffLL));
+
+    // ---- global -> LDS addressing (per lane, fixed for the whole K loop) ----
+    // A: wave-load q = j*NWAVES + wave covers rows [q*A_RPI, (q+1)*A_RPI); lane i writes LDS slot i,
+    // i.e. row q*A_RPI + i/A_CPR, physical chunk i%A_CPR, which must hold logical chunk p ^ swz.
+    const int a_row = wave * C::A_RPI + lane / C::A_CPR;                 // + j * NWAVES*A_RPI
+    const int a_chunk = (lane % C::A_CPR) ^ swz_a<C>(a_row);
+    const unsigned a_voff0 = (unsigned)(((m0 + a_row) * g.lda + k_begin + a_chunk * 8) * 2);
+    const unsigned a_step = (unsigned)(C::NWAVES * C::A_RPI * g.lda * 2);
+    const int a_kcol = k_begin + a_chunk * 8;                             // + kt*BK, compared with k_end
+    // B: wave-load q covers rows [q*B_RPI, (q+1)*B_RPI)
+    const int b_row = wave * C::B_RPI + lane / C::B_CPR;                  // + j * NWAVES*B_RPI
+    const int b_chunk = (lane % C::B_CPR) ^ swz_b<C>(b_row);
+    const bool b_col_ok = (n0 + b_chunk * 8) < g.N;
+    const unsigned b_voff0 = b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + n0 + b_chunk * 8) * 2) : OOB;
+    const unsigned b_step = (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
+    const unsigned b_kstep = (unsigned)(C::BK * g.ldb * 2);
+
+    auto load_tile = [&](int kt, int buf) {
+        char* sA = lds + buf * C::STAGE_BYTES;
+        char* sB = sA + C::A_BYTES;
+        const bool a_ok = (a_kcol + kt * C::BK) < k_end;
+        const unsigned av = a_ok ? a_voff0 + (unsigned)(kt * C::BK * 2) : OOB;
+#pragma unroll
+        for (int j = 0; j < C::A_LOADS; ++j) {
+            dma16(rsrcA, lds_addr_of(sA + (j * C::NWAVES + wave) * 1024), a_ok ? av + j * a_step : OOB);
+        }
+        const unsigned bv = b_voff0 + (b_col_ok ? (unsigned)kt * b_kstep : 0u);
+#pragma unroll
+        for (int j = 0; j < C::B_LOADS; ++j) {
+            dma16(rsrcB, lds_addr_of(sB + (j * C::NWAVES + wave) * 1024), b_col_ok ? bv + j * b_step : OOB);
+        }
+    };
+
+    // ---- LDS -> register addressing ----------------------------------------
+    // A fragment (fed as the MFMA "B" operand): lane holds A[m = l%32][8 consecutive k of half l/32]
+    const int fa_row = wm * C::WTM + (lane & 31);                         // + tm*32
+    const int fa_swz = swz_a<C>(fa_row);
+    const int fa_base = fa_row * (C::BK * 2);
+    // B fragment (fed as the MFMA "A" operand) through two transposing reads per 8 k-values
+    const int fb_krow = 8 * (lane >> 5) + ((lane & 15) >> 2);             // + 16*ks + 4*h
+    const int fb_swz = swz_b<C>(fb_krow);                                 // 16*ks + 4*h never changes k&3 nor (k>>1)&1 ... see static_assert below
+    const int fb_ncol = wn * C::WTN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // + tn*32
+    static_assert(C::BN >= 64, "swz_b for BN==64 uses bit 1 of k, unchanged by multiples of 4");
+
+    half8 fa[2][C::TM];
+    half8 fb[2][C::TN];
+    float16v acc[C::TM][C::TN];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    auto read_frags = [&](int buf, int ks, int slot) {
+        const char* sA = lds + buf * C::STAGE_BYTES;
+        const char* sB = sA + C::A_BYTES;
+        const int chunk = (2 * ks + (lane >> 5)) ^ fa_swz;
+#pragma unroll
+        for (int tm = 0; tm < C::TM; ++tm) {
+            fa[slot][tm] = *(const half8*)(sA + fa_base + tm * 32 * (C::BK * 2) + chunk * 16);
+        }
+#pragma unroll
+        for (int tn = 0; tn < C::TN; ++tn) {
+            const int n = fb_ncol + tn * 32;
+            const int pchunk = (n >> 3) ^ fb_swz;
+            const int off = pchunk * 16 + (n & 7) * 2;
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (16 * ks + fb_krow) * (C::BN * 2) + off));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (16 * ks + 4 + fb_krow) * (C::BN * 2) + off));
+            union { struct { short4v lo, hi; } s; half8 h; } u;
+            u.s.lo = lo;
+            u.s.hi = hi;
+            fb[slot][tn] = u.h;
+        }
+    };
+    auto mma = [&](int slot) {
+#pragma unroll
+        for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
+    };
+
+    // ---- main loop ----------------------------------------------------------
+    if (KT > 0) {
+#pragma unroll
+        for (int s = 0; s < C::STAGES; ++s)
+            if (s < KT) load_tile(s, s);
+        // tile 0 must have landed: at most the later prologue tiles may still be in flight
+        if (KT >= C::STAGES) wait_vmcnt<(C::STAGES - 1) * C::LOADS>(); else wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");
+        read_frags(0, 0, 0);
+
+        int buf = 0;
+        for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+            for (int ks = 0; ks < C::KS - 1; ++ks) {
+                read_frags(buf, ks + 1, (ks + 1) & 1);
+                mma(ks & 1);
+            }
+            // Every wave now holds its last fragments of tile kt in registers, so after the
+            // barrier buffer `buf` is free and tile kt+1 (issued STAGES-1 iterations ago) is visible.
+            if (kt + C::STAGES <= KT) wait_vmcnt<(C::STAGES - 2) * C::LOADS>(); else wait_vmcnt<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (kt + C::STAGES < KT) load_tile(kt + C::STAGES, buf);
+            const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+            if (kt + 1 < KT) read_frags(nbuf, 0, 0);
+            mma((C::KS - 1) & 1);
+            buf = nbuf;
+        }
+    }
+
+    // ---- epilogue: fp32 -> fp16 (round to nearest even), 8-byte stores -------
+    // acc[tm][tn][v]: row m = m0 + wm*WTM + tm*32 + l%32, columns n = n0 + wn*WTN + tn*32 + 8*(v/4) + 4*(l/32) + v%4
+    const int row_l = m0 + wm * C::WTM + (lane & 31);
+    const int col_l = n0 + wn * C::WTN + 4 * (lane >> 5);
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm) {
+        const int m = row_l + tm * 32;
+        if (m < g.M) {
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn) {
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int n = col_l + tn * 32 + vg * 8;
+                    if (n < g.N) {
+                        if (SPLITK) {
+                            float4v o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
+                            *(float4v*)(g.partial + ((size_t)split * g.M + m) * g.N + n) = o;
+                        } else {
+                            half4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[tm][tn][vg * 4 + e];
+                            *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace hgemm

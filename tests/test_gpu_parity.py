@@ -1,0 +1,234 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2512_02551_amd as hg  # noqa: E402
+import workloads as wl  # noqa: E402
+from oracle import hgemm_oracle as orc  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import assert_bit_exact, assert_close, run_hgemm, to_dev, to_host  # noqa: E402
+
+
+def all_mfma_specs(sk=1, gm=8):
+    out = []
+    for line in hg.spec_help().splitlines():
+        if "compiled" in line:
+            for tup in line.split(":")[1].split():
+                bm, bn, bk, wm, wn, st = (int(x) for x in tup.strip("()").split(","))
+                out.append(f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},sk={sk},gm={gm}")
+    assert out
+    return out
+
+
+# ---- configuration C1: 256^3 uniform[-1,1], seed 0 -------------------------------------------
+
+def test_c1_256_cubed_default_plan():
+    a, b = wl.c1_inputs()
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b)
+    print("C1 plan:", desc)
+    assert_close(c, ref, "C1 " + desc)
+
+
+# ---- every compiled specialisation, ragged shape, exact integers ------------------------------
+
+@pytest.mark.parametrize("shape", [(300, 264, 200), (33, 520, 328), (257, 72, 64)])
+def test_every_spec_bit_exact_on_small_integers_ragged(shape):
+    name, a, b = wl.exact_family_for(shape, seed=1)
+    ref = orc.hgemm(a, b)
+    for spec in all_mfma_specs():
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=4)
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all(), f"{desc}: wrote outside C"
+
+
+@pytest.mark.parametrize("sk", [2, 3, 5])
+def test_split_k_bit_exact_and_ordered(sk):
+    shape = (96, 136, 1000)
+    name, a, b = wl.exact_family_for(shape, seed=2)
+    ref = orc.hgemm(a, b)
+    for spec in all_mfma_specs(sk=sk):
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=2)
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all()
+
+
+def test_every_spec_real_inputs_within_tolerance():
+    shape = (520, 392, 712)
+    rng = np.random.default_rng(3)
+    a = wl.uniform_pm1(rng, shape[0], shape[2])
+    b = wl.uniform_pm1(rng, shape[2], shape[1])
+    ref = orc.hgemm(a, b)
+    for spec in all_mfma_specs() + all_mfma_specs(sk=3):
+        c, _, _, desc = run_hgemm(a, b, spec=spec)
+        assert_close(c, ref, desc)
+
+
+# ---- the paper's binary exact-match test (Section 2.3.2), several seeds ------------------------
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
+def test_binary_exact_match_below_2048(seed):
+    shape = (128, 192, 4096)
+    a, b = wl.binary_inputs(shape, seed=seed)
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b)
+    r = ref.astype(np.float64)
+    sel = r <= 2048
+    assert sel.mean() > 0.9 and (r > 0).mean() > 0.9
+    assert np.array_equal(c.astype(np.float64)[sel], r[sel]), desc
+
+
+def test_half_integer_inputs_exact_below_1024():
+    shape = (64, 128, 1024)
+    rng = np.random.default_rng(5)
+    a = wl.bernoulli(rng, shape[0], shape[2], 0.6, 0.5)
+    b = wl.bernoulli(rng, shape[2], shape[1], 0.6, 1.0)
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b)
+    sel = ref.astype(np.float64) < 1024
+    assert sel.all()
+    assert_bit_exact(c, ref, desc)
+
+
+# ---- tile order, tails, degenerate shapes -------------------------------------------------------
+
+@pytest.mark.parametrize("gm", [0, 1, 3, 8, 16])
+def test_tile_order_variants(gm):
+    shape = (40 * 32, 35 * 64, 64)          # 40 x 35 tiles of 32x64... many workgroups, not a multiple of 256
+    name, a, b = wl.exact_family_for(shape, seed=gm)
+    ref = orc.hgemm(a, b)
+    for spec in (f"mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,sk=1,gm={gm}", f"mfma,bm=32,bn=128,bk=64,wm=1,wn=4,st=4,sk=1,gm={gm}"):
+        c, _, _, desc = run_hgemm(a, b, spec=spec)
+        assert_bit_exact(c, ref, desc)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64), (1, 4096, 512), (16, 128, 4096), (7, 8, 8), (5, 72, 24), (64, 64, 8)])
+def test_small_m_and_tiny_shapes_default_plan(shape):
+    name, a, b = wl.exact_family_for(shape, seed=3)
+    ref = orc.hgemm(a, b)
+    c, before, after, desc = run_hgemm(a, b, guard=3)
+    if name == "binary":
+        sel = ref.astype(np.float64) <= 2048
+        assert np.array_equal(c[sel].view(np.uint16), ref[sel].view(np.uint16)), desc
+    else:
+        assert_bit_exact(c, ref, f"{shape} {desc}")
+    assert np.isnan(before).all() and np.isnan(after).all()
+
+
+@pytest.mark.parametrize("shape", [(3, 5, 7), (17, 9, 33), (65, 130, 257), (1, 1, 1), (129, 63, 100)])
+def test_unaligned_shapes_take_generic_kernel(shape):
+    M, N, K = shape
+    rng = np.random.default_rng(sum(shape))
+    a = wl.integers(rng, M, K, -3, 3)
+    b = wl.integers(rng, K, N, -3, 3)
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b)
+    assert desc == "generic"
+    assert_bit_exact(c, ref, f"{shape}")
+    # TN layout (B stored N x K) gives the same product
+    c2, _, _, desc2 = run_hgemm(a, np.ascontiguousarray(b.T), b_col_major=True)
+    assert desc2 == "generic"
+    assert_bit_exact(c2, ref, f"{shape} TN")
+
+
+def test_empty_and_k_zero():
+    # K = 0: C must become all zeros whatever it held
+    a = np.zeros((5, 0), dtype=np.float16)
+    b = np.zeros((0, 16), dtype=np.float16)
+    c, _, _, _ = run_hgemm(a, b, prefill=7.0)
+    assert c.shape == (5, 16) and not c.any()
+    # M = 0 / N = 0: nothing to do, nothing touched
+    with hg.Plan(0, 16, 8) as p:
+        assert p.run_status(None, None, None) == 0
+    with hg.Plan(4, 0, 8) as p:
+        assert p.run_status(None, None, None) == 0
+
+
+def test_beta_zero_semantics_nan_in_c_never_leaks():
+    a, b = wl.small_int_inputs((64, 64, 64), seed=9)
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b, prefill=float("nan"))
+    assert not np.isnan(c).any()
+    assert_bit_exact(c, ref, desc)
+
+
+def test_run_to_run_determinism_on_real_inputs():
+    shape = (384, 512, 2048)
+    rng = np.random.default_rng(21)
+    a = wl.uniform_pm1(rng, shape[0], shape[2])
+    b = wl.uniform_pm1(rng, shape[2], shape[1])
+    for spec in (None, "mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=4,sk=4,gm=8"):
+        c1, _, _, desc = run_hgemm(a, b, spec=spec)
+        c2, _, _, _ = run_hgemm(a, b, spec=spec)
+        assert np.array_equal(c1.view(np.uint16), c2.view(np.uint16)), desc
+
+
+def test_nan_and_inf_propagate_like_the_oracle():
+    a, b = wl.small_int_inputs((64, 64, 64), seed=4)
+    a = a.copy()
+    b = b.copy()
+    a[3, 5] = np.nan
+    a[10, 0] = np.inf
+    b[0, 7] = 0          # inf * 0 = NaN at C[10, 7]
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b)
+    assert np.array_equal(np.isnan(c), np.isnan(ref)), desc
+    fin = ~np.isnan(ref)
+    assert np.array_equal(c[fin].astype(np.float64), ref[fin].astype(np.float64))
+
+
+def test_overflow_rounds_to_infinity():
+    K = 64
+    a = np.full((32, K), 60.0, dtype=np.float16)
+    b = np.full((K, 64), 30.0, dtype=np.float16)       # 64 * 1800 = 115200 > 65504
+    ref = orc.hgemm(a, b)
+    c, _, _, _ = run_hgemm(a, b)
+    assert np.isinf(ref).all() and np.array_equal(c.view(np.uint16), ref.view(np.uint16))
+
+
+def test_leading_dimensions():
+    M, N, K = 96, 80, 72
+    lda, ldb, ldc = 88, 96, 104
+    rng = np.random.default_rng(8)
+    A = wl.integers(rng, M, lda, -2, 2)
+    B = wl.integers(rng, K, ldb, -2, 2)
+    ref = orc.hgemm(np.ascontiguousarray(A[:, :K]), np.ascontiguousarray(B[:, :N]))
+    dA, dB = to_dev(A), to_dev(B)
+    dC = torch.full((M, ldc), float("nan"), dtype=torch.float16, device="cuda")
+    lay = hg.Layouts.make(lda=lda, ldb=ldb, ldc=ldc)
+    for spec in (None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,sk=2,gm=8", "generic"):
+        dC.fill_(float("nan"))
+        with hg.Plan(M, N, K, lay, spec) as p:
+            p.run(dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            desc = p.describe()
+        out = to_host(dC)
+        assert_bit_exact(out[:, :N], ref, desc)
+        assert np.isnan(out[:, N:]).all(), desc + ": wrote into the padding of C"
+
+
+def test_error_paths():
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(-1, 8, 8)
+    assert e.value.status == 1
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(64, 64, 64, None, "mfma,bm=17,bn=64,bk=64,wm=2,wn=2,st=4")
+    assert e.value.status == 2
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(64, 64, 64, None, "nonsense")
+    assert e.value.status == 1
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(64, 64, 63, None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4")     # K not a multiple of 8
+    assert e.value.status == 2
+    lay = hg.Layouts.make()
+    lay.a = 1                                                                  # column-major A is not offered
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(64, 64, 64, lay)
+    assert e.value.status == 2
+    with hg.Plan(64, 64, 64) as p:
+        assert p.run_status(None, None, None) == 1                             # null pointers with work to do

@@ -1,0 +1,74 @@
+"""CPU-only checks: the library loads, exports every declared symbol, and its host-side logic
+(tile arithmetic, tile order) is right.  No kernel is launched here."""
+import os
+import re
+
+import pytest
+
+import paper_2512_02551_amd as hg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hg.lib_path()):
+        from paper_2512_02551_amd import build
+        build.build(force=True)
+    return hg.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "hgemm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(hgemm_[a-z_]+)\s*\(", header))
+    assert declared == set(hg.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    for s in range(6):
+        assert hg.status_string(s)
+    assert "gfx950" in hg.status_string(5)
+
+
+def test_padding_arithmetic_matches_the_papers_example(lib):
+    # Section 5.2: M = 8192, BM = 160 -> 52 tiles, 8320 rows
+    assert hg.tiles(8192, 160) == 52
+    assert hg.padded(8192, 160) == 8320
+    assert hg.tiles(0, 64) == 0 and hg.tiles(1, 64) == 1 and hg.tiles(64, 64) == 1 and hg.tiles(65, 64) == 2
+    assert hg.tiles(5, 0) == -1
+
+
+@pytest.mark.parametrize("tm,tn", [(1, 1), (3, 5), (32, 32), (16, 16), (40, 35), (7, 300), (300, 7), (64, 43), (1, 1000)])
+@pytest.mark.parametrize("group", [0, 1, 3, 8, 16])
+def test_tile_order_is_a_bijection(lib, tm, tn, group):
+    total = tm * tn
+    seen = [hg.tile_of_workgroup(w, tm, tn, group) for w in range(total)]
+    assert sorted(seen) == list(range(total))
+    assert hg.tile_of_workgroup(total, tm, tn, group) == -1
+
+
+def test_tile_order_keeps_an_xcd_on_a_compact_block(lib):
+    # 32 x 32 tiles, group 8: the 32 workgroups one XCD gets from a run of 256 ids
+    # (ids congruent mod 8) must cover 8 tile-rows x 4 tile-columns.
+    tm = tn = 32
+    for xcd in range(8):
+        tiles = [hg.tile_of_workgroup(w, tm, tn, 8) for w in range(xcd, 256, 8)]
+        rows = {t // tn for t in tiles}
+        cols = {t % tn for t in tiles}
+        assert len(rows) == 8 and len(cols) == 4
+    # and a whole run of 256 ids covers 8 rows x 32 columns
+    tiles = [hg.tile_of_workgroup(w, tm, tn, 8) for w in range(256)]
+    assert {t // tn for t in tiles} == set(range(8)) and {t % tn for t in tiles} == set(range(32))
+
+
+def test_candidates_and_help_are_consistent(lib):
+    specs = hg.candidates(4096, 4096, 4096)
+    assert specs and all(s.startswith("mfma,") for s in specs)
+    assert hg.candidates(3, 5, 7) == ["generic"]
+    text = hg.spec_help()
+    assert "generic" in text and "mfma" in text
+    skinny = hg.candidates(16, 4096, 4096)
+    assert any("sk=8" in s or "sk=16" in s for s in skinny)
