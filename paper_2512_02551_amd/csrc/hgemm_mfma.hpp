@@ -210,20 +210,23 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const unsigned b_step = (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
     const unsigned b_kstep = (unsigned)(C::BK * g.ldb * 2);
 
-    auto load_tile = [&](int kt, int buf) {
+    // One wave-load of tile kt: index j < A_LOADS is an A load, the rest are B loads.
+    auto dma_one = [&](int kt, int buf, int j) {
         char* sA = lds + buf * C::STAGE_BYTES;
         char* sB = sA + C::A_BYTES;
-        const bool a_ok = (a_kcol + kt * C::BK) < k_end;
-        const unsigned av = a_ok ? a_voff0 + (unsigned)(kt * C::BK * 2) : OOB;
-#pragma unroll
-        for (int j = 0; j < C::A_LOADS; ++j) {
-            dma16(rsrcA, lds_addr_of(sA + (j * C::NWAVES + wave) * 1024), a_ok ? av + j * a_step : OOB);
+        if (j < C::A_LOADS) {
+            const bool a_ok = (a_kcol + kt * C::BK) < k_end;
+            dma16(rsrcA, lds_addr_of(sA + (j * C::NWAVES + wave) * 1024),
+                  a_ok ? a_voff0 + (unsigned)(kt * C::BK * 2) + j * a_step : OOB);
+        } else {
+            const int jb = j - C::A_LOADS;
+            dma16(rsrcB, lds_addr_of(sB + (jb * C::NWAVES + wave) * 1024),
+                  b_col_ok ? b_voff0 + (unsigned)kt * b_kstep + jb * b_step : OOB);
         }
-        const unsigned bv = b_voff0 + (b_col_ok ? (unsigned)kt * b_kstep : 0u);
+    };
+    auto load_tile = [&](int kt, int buf) {
 #pragma unroll
-        for (int j = 0; j < C::B_LOADS; ++j) {
-            dma16(rsrcB, lds_addr_of(sB + (j * C::NWAVES + wave) * 1024), b_col_ok ? bv + j * b_step : OOB);
-        }
+        for (int j = 0; j < C::LOADS; ++j) dma_one(kt, buf, j);
     };
 
     // ---- LDS -> register addressing ----------------------------------------
@@ -233,9 +236,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int fa_base = fa_row * (C::BK * 2);
     // B fragment (fed as the MFMA "A" operand) through two transposing reads per 8 k-values
     const int fb_krow = 8 * (lane >> 5) + ((lane & 15) >> 2);             // + 16*ks + 4*h
-    const int fb_swz = swz_b<C>(fb_krow);                                 // 16*ks + 4*h never changes k&3 nor (k>>1)&1 ... see static_assert below
+    const int fb_swz = swz_b<C>(fb_krow);                                 // adding 16*ks + 4*h changes neither k&3 nor bit 1 of k
     const int fb_ncol = wn * C::WTN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // + tn*32
-    static_assert(C::BN >= 64, "swz_b for BN==64 uses bit 1 of k, unchanged by multiples of 4");
 
     half8 fa[2][C::TM];
     half8 fb[2][C::TN];
@@ -247,19 +249,19 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    auto read_frags = [&](int buf, int ks, int slot) {
+    // Fragment read number r of a k-step: r < TM reads A fragment r, the rest read B fragment r-TM.
+    constexpr int NREADS = C::TM + C::TN;
+    constexpr int NMMA = C::TM * C::TN;
+    auto read_one = [&](int buf, int ks, int slot, int r) {
         const char* sA = lds + buf * C::STAGE_BYTES;
         const char* sB = sA + C::A_BYTES;
-        const int chunk = (2 * ks + (lane >> 5)) ^ fa_swz;
-#pragma unroll
-        for (int tm = 0; tm < C::TM; ++tm) {
-            fa[slot][tm] = *(const half8*)(sA + fa_base + tm * 32 * (C::BK * 2) + chunk * 16);
-        }
-#pragma unroll
-        for (int tn = 0; tn < C::TN; ++tn) {
+        if (r < C::TM) {
+            const int chunk = (2 * ks + (lane >> 5)) ^ fa_swz;
+            fa[slot][r] = *(const half8*)(sA + fa_base + r * 32 * (C::BK * 2) + chunk * 16);
+        } else {
+            const int tn = r - C::TM;
             const int n = fb_ncol + tn * 32;
-            const int pchunk = (n >> 3) ^ fb_swz;
-            const int off = pchunk * 16 + (n & 7) * 2;
+            const int off = ((n >> 3) ^ fb_swz) * 16 + (n & 7) * 2;
             short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (16 * ks + fb_krow) * (C::BN * 2) + off));
             short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -270,15 +272,46 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             fb[slot][tn] = u.h;
         }
     };
-    auto mma = [&](int slot) {
+    auto read_frags = [&](int buf, int ks, int slot) {
 #pragma unroll
-        for (int tm = 0; tm < C::TM; ++tm)
+        for (int r = 0; r < NREADS; ++r) read_one(buf, ks, slot, r);
+    };
+    auto mma_one = [&](int slot, int i) {
+        const int tm = i / C::TN, tn = i % C::TN;
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
+    };
+
+    // One k-step with a pinned instruction order: matrix-core instruction i is followed by its
+    // share of the side work (fragment reads of the next k-step, and in the last k-step of a
+    // tile the global->LDS copies of a later tile), so that the side work issues in the shadow of
+    // the matrix cores instead of in a burst in front of them (the staggered prefetch of
+    // Section 5.3.4, taken to instruction granularity).
+    auto kstep = [&](int slot, int rbuf, int rks, bool do_reads, int dma_kt, int dma_buf, bool do_dma) {
+        constexpr int NSIDE_MAX = NREADS + C::LOADS;
+        const int nside = (do_reads ? NREADS : 0) + (do_dma ? C::LOADS : 0);
+        (void)NSIDE_MAX;
 #pragma unroll
-            for (int tn = 0; tn < C::TN; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
+        for (int i = 0; i < NMMA; ++i) {
+            mma_one(slot, i);
+            // side ops [lo, hi) go after MFMA i: spread nside ops evenly over the NMMA slots
+            const int lo = (i * nside) / NMMA, hi = ((i + 1) * nside) / NMMA;
+#pragma unroll
+            for (int t = 0; t < NSIDE_MAX; ++t) {
+                if (t >= lo && t < hi) {
+                    // fragment reads first (they are needed soonest), then the copies
+                    if (do_reads && t < NREADS) read_one(rbuf, rks, slot ^ 1, t);
+                    else dma_one(dma_kt, dma_buf, t - (do_reads ? NREADS : 0));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // ---- main loop ----------------------------------------------------------
+    // Tile kt lives in LDS buffer kt % STAGES.  In iteration kt the barrier sits in front of the
+    // last k-step: by then every wave holds its last fragments of tile kt in registers, so after
+    // the barrier buffer kt % STAGES is free for tile kt+STAGES, and tile kt+1 (copies issued
+    // STAGES-1 iterations earlier) is complete and visible to all waves.
     if (KT > 0) {
 #pragma unroll
         for (int s = 0; s < C::STAGES; ++s)
@@ -287,24 +320,34 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         if (KT >= C::STAGES) wait_vmcnt<(C::STAGES - 1) * C::LOADS>(); else wait_vmcnt<0>();
         asm volatile("s_barrier" ::: "memory");
         read_frags(0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 
         int buf = 0;
-        for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-            for (int ks = 0; ks < C::KS - 1; ++ks) {
-                read_frags(buf, ks + 1, (ks + 1) & 1);
-                mma(ks & 1);
-            }
-            // Every wave now holds its last fragments of tile kt in registers, so after the
-            // barrier buffer `buf` is free and tile kt+1 (issued STAGES-1 iterations ago) is visible.
-            if (kt + C::STAGES <= KT) wait_vmcnt<(C::STAGES - 2) * C::LOADS>(); else wait_vmcnt<0>();
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            if (kt + C::STAGES < KT) load_tile(kt + C::STAGES, buf);
+        int kt = 0;
+        // steady state: a later tile exists to be copied and a next tile exists to be read
+        for (; kt + C::STAGES < KT; ++kt) {
             const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-            if (kt + 1 < KT) read_frags(nbuf, 0, 0);
-            mma((C::KS - 1) & 1);
+#pragma unroll
+            for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
+            wait_vmcnt<(C::STAGES - 2) * C::LOADS>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            kstep((C::KS - 1) & 1, nbuf, 0, true, kt + C::STAGES, buf, true);
             buf = nbuf;
         }
+        // drain: no more copies to issue
+        for (; kt + 1 < KT; ++kt) {
+            const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+#pragma unroll
+            for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
+            wait_vmcnt<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            kstep((C::KS - 1) & 1, nbuf, 0, true, 0, 0, false);
+            buf = nbuf;
+        }
+        // last tile
+#pragma unroll
+        for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
+        kstep((C::KS - 1) & 1, 0, 0, false, 0, 0, false);
     }
 
     // ---- epilogue: fp32 -> fp16 (round to nearest even), 8-byte stores -------
