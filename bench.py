@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""HGEMM benchmark on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C1|C3|C4|C5] [--cold]
+
+A step is one pass of the whole hot path (plan lookup done beforehand, then hgemm_run for
+every shape of the workload) over inputs that already sit in HBM.  The default workload is
+the square sweep M=N=K in {1024, 2048, 4096, 8192} with entries N(0,1)/sqrt(K).  After W
+untimed steps, exactly K steps are timed between device synchronisations; every hgemm_run
+is also bracketed by events on the stream it is launched on, which gives the per-shape
+times the metric is built from.  The last line printed is one JSON object:
+
+  value        geometric mean over the workload's shapes of 2*M*N*K / (mean time per call), TFLOP/s
+  roofline     the dominant kernel (largest share of the step) against the published MI355X peak
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload on this host
+
+The timing protocol follows the paper's listing in Section 2.4.1 (events around the call on the
+current stream, synchronise on both sides); "--cold" rotates through enough operand sets that
+the 256 MiB last-level cache cannot hold them (the server-mode effect of Section 2.4.2).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+# HBM bytes per launch of the dominant kernel of the default workload (8192^3), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--cold", action="store_true", help="rotate operand sets so caches are cold")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--spec", default=None, help="force one specialisation for every shape (tuning aid)")
+    ap.add_argument("--table", action="store_true", help="print the per-shape table to stderr")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the roofline calibration kernels (MFMA-only loop, 1 GiB streaming read, "
+                         "128 MiB fill) -- kernels of known size for scaling profiler counters")
+    return ap.parse_args()
+
+
+def workload_shapes(name):
+    import workloads as wl
+
+    if name == "C1":
+        return [wl.C1_SHAPE], lambda s: wl.c1_inputs()
+    if name == "C2":
+        return list(wl.C2_SHAPES), wl.c2_inputs
+    if name == "C3":
+        return list(wl.C3_SHAPES), wl.c3_inputs
+    if name == "C4":
+        return wl.c4_shapes(), wl.c4_inputs
+    return list(wl.C5_SHAPES), wl.c5_inputs
+
+
+def cpu_baseline():
+    """The oracle as it stands, on a bounded sample of the default workload."""
+    import numpy as np
+
+    import workloads as wl
+    from oracle import hgemm_oracle as orc
+
+    rows = 1024
+    a1, b1 = wl.c2_inputs((1024, 1024, 1024))
+    a2, b2 = wl.c2_inputs((2048, 2048, 2048))
+    a2 = np.ascontiguousarray(a2[:rows])
+    t0 = time.perf_counter()
+    orc.hgemm(a1, b1)
+    orc.hgemm(a2, b2)
+    dt = time.perf_counter() - t0
+    flop = 2.0 * 1024 ** 3 + 2.0 * rows * 2048 * 2048
+    return {
+        "value": flop / dt * 1e-12,
+        "unit": "TFLOP/s",
+        "cores": orc.threads(),
+        "kind": "oracle",
+        "sample": "oracle on the full 1024^3 product plus the first 1024 rows of the 2048^3 product "
+                  f"of the square sweep ({dt:.1f} s of CPU work)",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures one GPU only (asked for --gpus {args.gpus}); "
+              "the library has no multi-GPU path, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2512_02551_amd as hg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    hg.load()          # fails loudly if libhgemm.so is missing: there is no fallback path
+
+    shapes, make_inputs = workload_shapes(args.workload)
+
+    # operands resident in HBM before anything is timed
+    def upload(x):
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+
+    sets = []
+    for (M, N, K) in shapes:
+        a, b = make_inputs((M, N, K))
+        n_sets = 1
+        if args.cold:
+            per_set = 2 * (M * K + K * N + M * N)
+            n_sets = max(2, min(64, math.ceil(768 * 2 ** 20 / per_set)))
+        group = []
+        da, db = upload(a), upload(b)
+        for i in range(n_sets):
+            group.append((da if i == 0 else da.clone(), db if i == 0 else db.clone(),
+                          torch.empty((M, N), dtype=torch.float16, device="cuda")))
+        plan = hg.Plan(M, N, K, None, args.spec)
+        sets.append({"shape": (M, N, K), "bufs": group, "plan": plan, "desc": plan.describe(),
+                     "info": plan.launch_info()})
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def one_step(step_idx, events=None):
+        for si, s in enumerate(sets):
+            a, b, c = s["bufs"][step_idx % len(s["bufs"])]
+            if events is not None:
+                e0, e1 = events[si]
+                e0.record(stream)
+                s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+                e1.record(stream)
+            else:
+                s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+
+    for w in range(args.warmup):
+        one_step(w)
+    torch.cuda.synchronize()
+
+    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sets]
+                  for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(args.warmup + k, all_events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_shape = []
+    for si, s in enumerate(sets):
+        ts = np.array([all_events[k][si][0].elapsed_time(all_events[k][si][1]) for k in range(args.steps)])
+        M, N, K = s["shape"]
+        flop = 2.0 * M * N * K
+        byts = 2.0 * (M * K + K * N + M * N)
+        mean_ms = float(ts.mean())
+        per_shape.append({
+            "shape": [M, N, K], "spec": s["desc"], "workgroups": s["info"]["workgroups"],
+            "mean_us": mean_ms * 1e3, "median_us": float(np.median(ts)) * 1e3, "min_us": float(ts.min()) * 1e3,
+            "tflops": flop / mean_ms * 1e-9, "gbs": byts / mean_ms * 1e-6,
+            "frac_mfma_peak": flop / mean_ms * 1e-9 / PEAK_FP16_TFLOPS,
+            "frac_hbm_peak": byts / mean_ms * 1e-6 / PEAK_HBM_GBS,
+            "ai_flop_per_byte": flop / byts,
+        })
+    geomean = math.exp(sum(math.log(p["tflops"]) for p in per_shape) / len(per_shape))
+    total_flop = sum(2.0 * m * n * k for (m, n, k) in shapes)
+
+    # dominant kernel: the launch with the largest share of the step
+    dom = max(per_shape, key=lambda p: p["mean_us"])
+    M, N, K = dom["shape"]
+    ridge = PEAK_FP16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if dom["ai_flop_per_byte"] >= ridge:
+        roofline = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": dom["tflops"] / PEAK_FP16_TFLOPS}
+    else:
+        roofline = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": dom["gbs"] / PEAK_HBM_GBS}
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((M, N, K))
+    roofline["kernel"] = f"{M}x{N}x{K} [{dom['spec']}]"
+    roofline["avg_launch_us"] = dom["mean_us"]
+
+    if args.table:
+        for p in per_shape:
+            print("{:>18s}  {:9.1f} us  {:8.1f} TFLOP/s ({:4.1f}% MFMA)  {:8.1f} GB/s ({:4.1f}% HBM)  {}".format(
+                "x".join(map(str, p["shape"])), p["mean_us"], p["tflops"], 100 * p["frac_mfma_peak"], p["gbs"],
+                100 * p["frac_hbm_peak"], p["spec"]), file=sys.stderr)
+
+    out = {
+        "metric": "HGEMM TFLOP/s geomean over (M,N,K) grid",
+        "value": geomean,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 inputs/outputs, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": {"C1": "single 256^3, uniform[-1,1]",
+                         "C2": "square HGEMM sweep M=N=K in {1024,2048,4096,8192}, entries N(0,1)/sqrt(K)",
+                         "C3": "LLM-projection skinny shapes, A~N(0,1), B~N(0,0.02^2)",
+                         "C4": "200-shape grid from {64..12288}^3, uniform[-1,1]",
+                         "C5": "16384x16384x{8192,16384}, uniform[-1,1]"}[args.workload],
+            "layout": "NN row-major", "cache": "cold" if args.cold else "warm",
+            "aggregate_tflops": total_flop * args.steps / wall * 1e-12,
+        },
+        "roofline": roofline,
+        "per_shape": per_shape,
+    }
+    if args.calibrate:
+        ms, flop = hg.calibrate_mfma(20000, sh)
+        buf = torch.ones(1 << 28, dtype=torch.int32, device="cuda")           # 1 GiB
+        hg.calibrate_hbm_read(buf.data_ptr(), buf.numel() * 4, sh)            # warm-up (also fills no cache: 1 GiB > 256 MiB)
+        ms_r = hg.calibrate_hbm_read(buf.data_ptr(), buf.numel() * 4, sh)
+        cz = torch.empty((8192, 8192), dtype=torch.float16, device="cuda")
+        with hg.Plan(8192, 8192, 0) as pz:                                    # K = 0: a pure 128 MiB fill of C
+            pz.run(None, None, cz.data_ptr(), sh)
+            torch.cuda.synchronize()
+        out["calibration"] = {"mfma_only_tflops": flop / ms * 1e-9, "stream_read_gbs": buf.numel() * 4 / ms_r * 1e-6,
+                              "read_kernel_bytes": buf.numel() * 4, "fill_kernel_bytes": 8192 * 8192 * 2}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    for s in sets:
+        s["plan"].destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
