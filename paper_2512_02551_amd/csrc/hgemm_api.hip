@@ -26,12 +26,20 @@ struct MfmaEntry {
     int threads, lds_bytes;
     void (*plain)(GemmArgs);
     void (*splitk)(GemmArgs);
+    void (*plain_tn)(GemmArgs);
+    void (*splitk_tn)(GemmArgs);
+    void (*streamk)(GemmArgs);
+    void (*streamk_tn)(GemmArgs);
+    void (*fixup)(GemmArgs);
 };
 
 template <class C> static MfmaEntry make_entry()
 {
     return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::THREADS, C::LDS_BYTES,
-                     mfma_gemm_kernel<C, false>, mfma_gemm_kernel<C, true>};
+                     mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
+                     mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
+                     mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
+                     streamk_fixup_kernel<C::BM, C::BN, C::BK>};
 }
 
 #define HGEMM_MFMA_CONFIGS(X)                                                                    \
@@ -52,7 +60,17 @@ template <class C> static MfmaEntry make_entry()
     X(32, 256, 64, 1, 4, 4)                                                                      \
     X(32, 128, 64, 1, 4, 4)                                                                      \
     X(32, 128, 128, 1, 4, 4)                                                                     \
-    X(256, 256, 64, 2, 4, 2)
+    X(256, 256, 64, 2, 4, 2)                                                                     \
+    X(256, 256, 64, 4, 2, 2)                                                                     \
+    X(256, 256, 32, 2, 4, 3)                                                                     \
+    X(256, 256, 32, 2, 4, 4)                                                                     \
+    X(256, 256, 32, 2, 4, 5)                                                                     \
+    X(256, 256, 32, 2, 2, 5)                                                                     \
+    X(256, 128, 64, 2, 4, 3)                                                                     \
+    X(128, 256, 64, 2, 4, 3)                                                                     \
+    X(256, 128, 64, 4, 2, 3)                                                                     \
+    X(256, 128, 32, 2, 4, 6)                                                                     \
+    X(128, 256, 32, 2, 4, 6)
 
 static const std::vector<MfmaEntry>& registry()
 {
@@ -71,14 +89,17 @@ struct Spec {
     int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0, st = 0;
     int sk = 1;     // split-K factor
     int gm = 8;     // tile-order group height; 0 = row-major
+    int tb = 0;     // 1 = transpose row-major B into the workspace first, then run the K-contiguous (TN) kernel
+    int sm = 0;     // 1 = stream-K: whole waves of tiles data-parallel, the rest shared by K-tile iterations
 };
 
 static std::string spec_to_string(const Spec& s)
 {
     char buf[160];
     if (s.fam == FAM_GENERIC) return "generic";
-    snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,sk=%d,gm=%d", s.bm, s.bn, s.bk, s.wm, s.wn,
-             s.st, s.sk, s.gm);
+    snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
+             s.st, s.sk, s.gm, s.tb ? ",tb=1" : "");
+    if (s.sm) strncat(buf, ",sm=1", sizeof buf - strlen(buf) - 1);
     return buf;
 }
 
@@ -114,9 +135,11 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "st") sp.st = (int)v;
         else if (key == "sk") sp.sk = (int)v;
         else if (key == "gm") sp.gm = (int)v;
+        else if (key == "tb") sp.tb = (int)v;
+        else if (key == "sm") sp.sm = (int)v;
         else return false;
     }
-    if (sp.sk < 1) return false;
+    if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || (sp.sm && sp.sk > 1)) return false;
     *out = sp;
     return true;
 }
@@ -138,8 +161,10 @@ struct hgemm_plan_s {
     Spec spec;
     const MfmaEntry* entry;     // null for the generic family
     GemmArgs args;              // pointers filled in at run time
-    void* workspace;
+    void* workspace;            // [transposed B (when spec.tb)] [split-K partial sums]
     size_t workspace_bytes;
+    size_t partial_offset;      // byte offset of the partial sums inside the workspace
+    bool tn_kernel;             // the MFMA kernel reads B with K contiguous
     int device;
 };
 
@@ -147,12 +172,13 @@ namespace {
 
 bool fast_path_ok(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l)
 {
-    if (l.b != HGEMM_ROW_MAJOR) return false;
     if (N % 8 || K % 8 || l.lda % 8 || l.ldb % 8 || l.ldc % 8) return false;
     // buffer offsets are 32-bit and bit 31 marks "out of range": keep every operand, including
     // the rows a padded tile may address, below 2 GiB
     const int64_t lim = (int64_t)1 << 31;
-    if ((M + 512) * l.lda * 2 >= lim || (K + 512) * l.ldb * 2 >= lim || M * l.ldc * 2 >= ((int64_t)1 << 33)) return false;
+    const int64_t b_rows = (l.b == HGEMM_ROW_MAJOR) ? K : N;
+    if ((M + 512) * l.lda * 2 >= lim || (b_rows + 512) * l.ldb * 2 >= lim || M * l.ldc * 2 >= ((int64_t)1 << 33)) return false;
+    if ((N + 512) * K * 2 >= lim) return false;      // also the transposed copy of B, should a plan ask for one
     if (M >= (1 << 24) || N >= (1 << 24) || K >= (1 << 24)) return false;
     return true;
 }
@@ -208,21 +234,29 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     p->entry = nullptr;
     p->workspace = nullptr;
     p->workspace_bytes = 0;
+    p->partial_offset = 0;
+    p->tn_kernel = false;
     memset(&p->args, 0, sizeof p->args);
     if (s.fam == FAM_GENERIC) return HGEMM_OK;
     const MfmaEntry* e = find_entry(s);
     if (!e) return HGEMM_ERR_UNSUPPORTED;
     if (!fast_path_ok(M, N, K, p->lay)) return HGEMM_ERR_UNSUPPORTED;
+    if (s.tb && p->lay.b != HGEMM_ROW_MAJOR) return HGEMM_ERR_UNSUPPORTED;
+    p->tn_kernel = s.tb || p->lay.b == HGEMM_COL_MAJOR;
     p->entry = e;
     // dynamic LDS beyond 64 KiB has to be requested per kernel function
     if (hipFuncSetAttribute((const void*)e->plain, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
+        hipFuncSetAttribute((const void*)e->splitk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->plain_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->splitk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->streamk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->streamk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return HGEMM_ERR_LAUNCH;
     }
     GemmArgs& a = p->args;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
-    a.lda = (int)p->lay.lda; a.ldb = (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
+    a.lda = (int)p->lay.lda; a.ldb = s.tb ? (int)K : (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
     a.tiles_m = (int)((M + e->bm - 1) / e->bm);
     a.tiles_n = (int)((N + e->bn - 1) / e->bn);
     if ((int64_t)a.tiles_m * a.tiles_n >= ((int64_t)1 << 31)) return HGEMM_ERR_UNSUPPORTED;
@@ -237,14 +271,41 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     s.sk = (int)sk;
     a.splits = (int)sk;
     a.k_per_split = (int)(per * e->bk);
-    if (sk > 1) {
-        p->workspace_bytes = (size_t)sk * (size_t)M * (size_t)N * sizeof(float);
+    // stream-K geometry
+    a.dp_tiles = a.tiles_m * a.tiles_n;
+    a.sk_workers = 0;
+    a.sk_iters_per_worker = 1;
+    a.sk_total_iters = 0;
+    if (s.sm) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, p->device) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
+        const int64_t G = std::max(1, prop.multiProcessorCount);
+        const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+        const int64_t dp = (tiles / G) * G;
+        if (dp == tiles) {
+            s.sm = 0;                                   // whole waves only: nothing to stream
+        } else {
+            const int64_t total = (tiles - dp) * ktiles;
+            const int64_t ipw = (total + G - 1) / G;
+            a.dp_tiles = (int)dp;
+            a.sk_iters_per_worker = (int)ipw;
+            a.sk_total_iters = (int)total;
+            a.sk_workers = (int)((total + ipw - 1) / ipw);
+        }
+    }
+    size_t bt_bytes = s.tb ? (((size_t)N * (size_t)K * 2 + 255) / 256) * 256 : 0;
+    size_t partial_bytes = sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
+    if (s.sm) partial_bytes = (size_t)2 * a.sk_workers * e->bm * e->bn * sizeof(float);
+    p->partial_offset = bt_bytes;
+    p->workspace_bytes = bt_bytes + partial_bytes;
+    if (p->workspace_bytes) {
         if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
             (void)hipGetLastError();
             p->workspace = nullptr;
+            p->workspace_bytes = 0;
             return HGEMM_ERR_ALLOC;
         }
-        a.partial = (float*)p->workspace;
+        if (partial_bytes) a.partial = (float*)((char*)p->workspace + bt_bytes);
     }
     return HGEMM_OK;
 }
@@ -291,7 +352,9 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
             p->spec = Spec();
             st = finish_plan(p);
         } else {
-            if (!table_lookup(M, N, K, &p->spec) || !(l.lda == K && l.ldb == N && l.ldc == N)) p->spec = heuristic(M, N, K);
+            const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
+            if (!table_lookup(M, N, K, &p->spec) || !packed) p->spec = heuristic(M, N, K);
+            if (l.b == HGEMM_COL_MAJOR) p->spec.tb = 0;      // B already has K contiguous
             st = finish_plan(p);
             if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
                 p->spec = heuristic(M, N, K);
@@ -360,15 +423,29 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     a.C = (_Float16*)C;
     const MfmaEntry* e = plan->entry;
     const unsigned wgs = (unsigned)(a.tiles_m * a.tiles_n);
-    if (a.splits > 1) {
-        hipLaunchKernelGGL(e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes, stream, a);
+    if (plan->spec.tb) {
+        // B (K x N, row-major) -> workspace (N x K, row-major), then the K-contiguous kernel
+        hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, stream,
+                           (const _Float16*)B, (_Float16*)plan->workspace, (int)K, (int)N, (int)plan->lay.ldb);
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        a.B = (const _Float16*)plan->workspace;
+    }
+    if (plan->spec.sm) {
+        hipLaunchKernelGGL(plan->tn_kernel ? e->streamk_tn : e->streamk, dim3((unsigned)(a.dp_tiles + a.sk_workers)), dim3(e->threads),
+                           e->lds_bytes, stream, a);
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        hipLaunchKernelGGL(e->fixup, dim3(wgs - (unsigned)a.dp_tiles), dim3(256), 0, stream, a);
+    } else if (a.splits > 1) {
+        hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_tn : e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes,
+                           stream, a);
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
         const int64_t quads = M * (N / 4);
         const int blocks = (int)std::min<int64_t>((quads + 255) / 256, 2048);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float*)plan->workspace, (_Float16*)C,
-                           (int)M, (int)N, (int)plan->lay.ldc, a.splits);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                           (const float*)((const char*)plan->workspace + plan->partial_offset), (_Float16*)C, (int)M, (int)N,
+                           (int)plan->lay.ldc, a.splits);
     } else {
-        hipLaunchKernelGGL(e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
+        hipLaunchKernelGGL(plan->tn_kernel ? e->plain_tn : e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     }
     return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
 }
@@ -412,7 +489,8 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
     if (!plan) return HGEMM_ERR_INVALID_ARG;
     int64_t wg, lds, th;
     if (plan->entry) {
-        wg = (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
+        wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
+                           : (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
         lds = plan->entry->lds_bytes;
         th = plan->entry->threads;
     } else {
@@ -433,9 +511,12 @@ const char* hgemm_spec_help(void)
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,sk=SPLITS][,gm=GROUP]\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
-            "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major)\n"
+            "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
+            "    tb = 1: copy row-major B transposed into the workspace first and run the K-contiguous kernel,\n"
+            "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
+            "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
             "    compiled (bm,bn,bk,wm,wn,st):";
         for (const MfmaEntry& e : registry()) {
             char b[64];
@@ -475,6 +556,12 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                     sks.push_back(sk);
                 }
             }
+            if (t % CUS != 0 && ktiles >= 4 && e.bm >= 64 && e.bn >= 64) {
+                Spec s;
+                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.sk = 1; s.gm = 8; s.sm = 1;
+                out += spec_to_string(s);
+                out += "\n";
+            }
             for (int sk : sks) {
                 for (int gm : {8, 0, 4, 16}) {
                     if (gm != 8 && (t < 2 * CUS)) continue;      // order matters only when tiles outnumber CUs
@@ -482,6 +569,13 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                     s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
+                    // row-major B, tall problem: paying one transposing copy of B can be cheaper than
+                    // transposing reads in every workgroup
+                    if (l.b == HGEMM_ROW_MAJOR && gm == 8 && M >= 1024 && e.bm >= 128 && e.bn >= 128) {
+                        s.tb = 1;
+                        out += spec_to_string(s);
+                        out += "\n";
+                    }
                 }
             }
         }

@@ -53,6 +53,34 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 }
 
+// out (N x K, row-major, packed) = transpose of in (K x N, row-major, leading dimension ld).
+// 64 x 64 tiles through LDS; 16-byte global loads and stores, K and N multiples of 8.
+__global__ __launch_bounds__(256) void transpose_kernel(const _Float16* __restrict__ in, _Float16* __restrict__ out, int K, int N, int ld)
+{
+    __shared__ _Float16 tile[64][64 + 8];      // +8 halves: consecutive rows start 4 banks apart
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    // load: thread t reads 8 consecutive n of rows r and r+32
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = (t >> 3) + 32 * h, c = (t & 7) * 8;
+        half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k0 + r < K && n0 + c < N) v = *(const half8*)(in + (size_t)(k0 + r) * ld + n0 + c);
+        *(half8*)&tile[r][c] = v;
+    }
+    __syncthreads();
+    // store: thread t writes 8 consecutive k of output rows n and n+32
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int n = (t >> 3) + 32 * h, kc = (t & 7) * 8;
+        half8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = tile[kc + e][n];
+        if (n0 + n < N && k0 + kc < K) *(half8*)(out + (size_t)(n0 + n) * K + k0 + kc) = v;
+    }
+}
+
 // C = 0 for K == 0 (the empty sum), any ldc.
 __global__ __launch_bounds__(256) void zero_c_kernel(_Float16* __restrict__ C, int64_t M, int64_t N, int64_t ldc)
 {

@@ -59,7 +59,16 @@ struct GemmArgs {
     int swizzle;         // group height in tiles for the tile order; 0 = row-major
     int k_per_split;     // K range of one split, a multiple of BK (== K rounded up when not split)
     int splits;
+    // stream-K: the first dp_tiles tiles (in tile order) get one workgroup each; the K-tile
+    // iterations of the remaining tiles are dealt evenly to sk_workers more workgroups
+    int dp_tiles;
+    int sk_workers;
+    int sk_iters_per_worker;
+    int sk_total_iters;  // (tiles - dp_tiles) * ceil(K / BK)
 };
+
+// Kernel modes: one full-K tile per workgroup; split-K (grid.y = split); stream-K.
+enum { MODE_PLAIN = 0, MODE_SPLITK = 1, MODE_STREAMK = 2 };
 
 // ---------------------------------------------------------------------------
 // Tile order.  Hardware deals workgroup ids round-robin to the 8 XCDs, each
@@ -173,26 +182,63 @@ template <int N> __device__ inline void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <class C, bool SPLITK>
+// TN = B stored column-major, i.e. as an N x K row-major array (Section 2.2.2): then B tiles are
+// staged and read exactly like A tiles (K contiguous), with no transposing read.
+template <class C, int MODE, bool TN>
 __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    constexpr bool SPLITK = MODE == MODE_SPLITK;
+    constexpr bool STREAMK = MODE == MODE_STREAMK;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int split = SPLITK ? blockIdx.y : 0;
 
-    const int tile = (int)tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, g.swizzle);
+    // Stream-K bookkeeping (Section 5 of the paper has no counterpart; the scheme is: workgroups
+    // [0, dp_tiles) compute one whole tile each, workgroup dp_tiles + w takes the K-tile iterations
+    // [w*ipw, (w+1)*ipw) of the remaining tiles, laid end to end).  A worker's range is cut into
+    // segments at tile boundaries; a segment that covers a whole tile is stored to C directly, the
+    // others go to the workspace as fp32 partial tiles (slot 2w for the worker's first segment,
+    // 2w+1 for a later one) and are summed in k order by streamk_fixup_kernel.
+    const int kt_per_tile = STREAMK ? (g.K + C::BK - 1) / C::BK : 0;
+    int sk_iter = 0, sk_end = 0;
+    bool sk_worker = false;
+    if (STREAMK && (int)blockIdx.x >= g.dp_tiles) {
+        sk_worker = true;
+        const int w = (int)blockIdx.x - g.dp_tiles;
+        sk_iter = w * g.sk_iters_per_worker;
+        sk_end = min(sk_iter + g.sk_iters_per_worker, g.sk_total_iters);
+        if (sk_iter >= sk_end) return;
+    }
+    bool first_segment = true;
+
+  for (;;) {       // one pass per segment; a single pass unless MODE_STREAMK
+    int tile_id, k_begin, k_end;
+    bool to_partial = SPLITK;
+    if (STREAMK && sk_worker) {
+        const int t = sk_iter / kt_per_tile;
+        const int kt0 = sk_iter - t * kt_per_tile;
+        const int kt1 = min(kt_per_tile, kt0 + (sk_end - sk_iter));
+        tile_id = g.dp_tiles + t;
+        k_begin = kt0 * C::BK;
+        k_end = min(g.K, kt1 * C::BK);
+        to_partial = !(kt0 == 0 && kt1 == kt_per_tile);
+        sk_iter += kt1 - kt0;
+    } else {
+        tile_id = blockIdx.x;
+        k_begin = split * g.k_per_split;
+        k_end = min(g.K, k_begin + g.k_per_split);
+    }
+    const int tile = (int)tile_of_workgroup(tile_id, g.tiles_m, g.tiles_n, g.swizzle);
     const int m0 = (tile / g.tiles_n) * C::BM;
     const int n0 = (tile % g.tiles_n) * C::BN;
-    const int split = SPLITK ? blockIdx.y : 0;
-    const int k_begin = split * g.k_per_split;
-    const int k_end = min(g.K, k_begin + g.k_per_split);
     const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
 
     const unsigned OOB = 0x80000000u;        // beyond every num_records the host admits
     const int4v rsrcA = make_rsrc(g.A, (unsigned)min((long long)g.M * g.lda * 2, 0x7fffffffLL));
-    const int4v rsrcB = make_rsrc(g.B, (unsigned)min((long long)k_end * g.ldb * 2, 0x7fffffffLL));
+    const int4v rsrcB = make_rsrc(g.B, (unsigned)min((long long)(TN ? g.N : k_end) * g.ldb * 2, 0x7fffffffLL));
 
     // ---- global -> LDS addressing (per lane, fixed for the whole K loop) ----
     // A: wave-load q = j*NWAVES + wave covers rows [q*A_RPI, (q+1)*A_RPI); lane i writes LDS slot i,
@@ -202,13 +248,16 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const unsigned a_voff0 = (unsigned)(((m0 + a_row) * g.lda + k_begin + a_chunk * 8) * 2);
     const unsigned a_step = (unsigned)(C::NWAVES * C::A_RPI * g.lda * 2);
     const int a_kcol = k_begin + a_chunk * 8;                             // + kt*BK, compared with k_end
-    // B: wave-load q covers rows [q*B_RPI, (q+1)*B_RPI)
-    const int b_row = wave * C::B_RPI + lane / C::B_CPR;                  // + j * NWAVES*B_RPI
-    const int b_chunk = (lane % C::B_CPR) ^ swz_b<C>(b_row);
-    const bool b_col_ok = (n0 + b_chunk * 8) < g.N;
-    const unsigned b_voff0 = b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + n0 + b_chunk * 8) * 2) : OOB;
-    const unsigned b_step = (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
-    const unsigned b_kstep = (unsigned)(C::BK * g.ldb * 2);
+    // B, row-major (NN): wave-load q covers k-rows [q*B_RPI, (q+1)*B_RPI) of the BK x BN tile.
+    // B, column-major (TN): the tile is BN x BK with K contiguous and is addressed like the A tile.
+    const int b_row = TN ? wave * C::A_RPI + lane / C::A_CPR : wave * C::B_RPI + lane / C::B_CPR;
+    const int b_chunk = TN ? (lane % C::A_CPR) ^ swz_a<C>(b_row) : (lane % C::B_CPR) ^ swz_b<C>(b_row);
+    const bool b_col_ok = TN ? true : (n0 + b_chunk * 8) < g.N;
+    const unsigned b_voff0 = TN ? (unsigned)(((n0 + b_row) * g.ldb + k_begin + b_chunk * 8) * 2)
+                                : (b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + n0 + b_chunk * 8) * 2) : OOB);
+    const unsigned b_step = TN ? (unsigned)(C::NWAVES * C::A_RPI * g.ldb * 2) : (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
+    const unsigned b_kstep = TN ? (unsigned)(C::BK * 2) : (unsigned)(C::BK * g.ldb * 2);
+    const int b_kcol = k_begin + b_chunk * 8;                             // TN only: + kt*BK, compared with k_end
 
     // One wave-load of tile kt: index j < A_LOADS is an A load, the rest are B loads.
     auto dma_one = [&](int kt, int buf, int j) {
@@ -220,8 +269,9 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
                   a_ok ? a_voff0 + (unsigned)(kt * C::BK * 2) + j * a_step : OOB);
         } else {
             const int jb = j - C::A_LOADS;
+            const bool b_ok = TN ? (b_kcol + kt * C::BK) < k_end : b_col_ok;
             dma16(rsrcB, lds_addr_of(sB + (jb * C::NWAVES + wave) * 1024),
-                  b_col_ok ? b_voff0 + (unsigned)kt * b_kstep + jb * b_step : OOB);
+                  b_ok ? b_voff0 + (unsigned)kt * b_kstep + jb * b_step : OOB);
         }
     };
     auto load_tile = [&](int kt, int buf) {
@@ -238,6 +288,10 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int fb_krow = 8 * (lane >> 5) + ((lane & 15) >> 2);             // + 16*ks + 4*h
     const int fb_swz = swz_b<C>(fb_krow);                                 // adding 16*ks + 4*h changes neither k&3 nor bit 1 of k
     const int fb_ncol = wn * C::WTN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // + tn*32
+    // TN: B fragment read like an A fragment from the BN x BK tile
+    const int ft_row = wn * C::WTN + (lane & 31);                         // + tn*32
+    const int ft_swz = swz_a<C>(ft_row);
+    const int ft_base = ft_row * (C::BK * 2);
 
     half8 fa[2][C::TM];
     half8 fb[2][C::TN];
@@ -258,6 +312,10 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         if (r < C::TM) {
             const int chunk = (2 * ks + (lane >> 5)) ^ fa_swz;
             fa[slot][r] = *(const half8*)(sA + fa_base + r * 32 * (C::BK * 2) + chunk * 16);
+        } else if (TN) {
+            const int tn = r - C::TM;
+            const int chunk = (2 * ks + (lane >> 5)) ^ ft_swz;
+            fb[slot][tn] = *(const half8*)(sB + ft_base + tn * 32 * (C::BK * 2) + chunk * 16);
         } else {
             const int tn = r - C::TM;
             const int n = fb_ncol + tn * 32;
@@ -352,18 +410,26 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 
     // ---- epilogue: fp32 -> fp16 (round to nearest even), 8-byte stores -------
     // acc[tm][tn][v]: row m = m0 + wm*WTM + tm*32 + l%32, columns n = n0 + wn*WTN + tn*32 + 8*(v/4) + 4*(l/32) + v%4
-    const int row_l = m0 + wm * C::WTM + (lane & 31);
-    const int col_l = n0 + wn * C::WTN + 4 * (lane >> 5);
+    const int row_t = wm * C::WTM + (lane & 31);           // tile-local
+    const int col_t = wn * C::WTN + 4 * (lane >> 5);
+    float* sk_slot = nullptr;
+    if (STREAMK && to_partial)
+        sk_slot = g.partial + ((size_t)2 * ((int)blockIdx.x - g.dp_tiles) + (first_segment ? 0 : 1)) * (size_t)(C::BM * C::BN);
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm) {
-        const int m = row_l + tm * 32;
-        if (m < g.M) {
+        const int m = m0 + row_t + tm * 32;
+        if (m < g.M || (STREAMK && to_partial)) {
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn) {
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg) {
-                    const int n = col_l + tn * 32 + vg * 8;
-                    if (n < g.N) {
+                    const int n = n0 + col_t + tn * 32 + vg * 8;
+                    if (STREAMK && to_partial) {
+                        float4v o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
+                        *(float4v*)(sk_slot + (row_t + tm * 32) * C::BN + col_t + tn * 32 + vg * 8) = o;
+                    } else if (n < g.N) {
                         if (SPLITK) {
                             float4v o;
 #pragma unroll
@@ -379,6 +445,47 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
                 }
             }
         }
+    }
+    if (!(STREAMK && sk_worker) || sk_iter >= sk_end) break;
+    first_segment = false;
+    // the next segment's copies reuse the LDS buffers: every wave must be done reading them
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+}
+
+// Stream-K second pass: one workgroup per tile that stream-K workers shared.  Sums the fp32
+// partial tiles of the workers that touched the tile, in increasing k (= increasing worker)
+// order, rounds once to fp16 and stores the in-range part of the tile.
+template <int BM, int BN, int BK>
+__global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmArgs g)
+{
+    const int kt_per_tile = (g.K + BK - 1) / BK;
+    const int t = blockIdx.x;                                   // index among the stream-K tiles
+    const int it0 = t * kt_per_tile, it1 = it0 + kt_per_tile;   // this tile's iteration range
+    const int ipw = g.sk_iters_per_worker;
+    const int w_first = it0 / ipw, w_last = (it1 - 1) / ipw;
+    if (w_first == w_last) {
+        // a single worker saw the whole tile: it stored C itself unless it saw only part of it
+        const int wb = w_first * ipw, we = min(wb + ipw, g.sk_total_iters);
+        if (wb <= it0 && we >= it1) return;
+    }
+    const int tile = (int)tile_of_workgroup(g.dp_tiles + t, g.tiles_m, g.tiles_n, g.swizzle);
+    const int m0 = (tile / g.tiles_n) * BM;
+    const int n0 = (tile % g.tiles_n) * BN;
+    for (int q = threadIdx.x; q < BM * BN / 4; q += 256) {
+        const int r = q / (BN / 4), c = (q % (BN / 4)) * 4;
+        if (m0 + r >= g.M || n0 + c >= g.N) continue;
+        float4v sum = {0.f, 0.f, 0.f, 0.f};
+        for (int w = w_first; w <= w_last; ++w) {
+            const int wb = w * ipw;
+            const int s0 = max(wb, it0);
+            const int slot = 2 * w + (s0 == wb ? 0 : 1);
+            sum += *(const float4v*)(g.partial + (size_t)slot * (BM * BN) + r * BN + c);
+        }
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
+        *(half4*)(g.C + (size_t)(m0 + r) * g.ldc + n0 + c) = o;
     }
 }
 

@@ -47,6 +47,74 @@ def test_every_spec_bit_exact_on_small_integers_ragged(shape):
         assert np.isnan(before).all() and np.isnan(after).all(), f"{desc}: wrote outside C"
 
 
+@pytest.mark.parametrize("shape", [(300, 264, 200), (33, 520, 328)])
+def test_every_spec_tn_layout_bit_exact(shape):
+    """B stored column-major (N x K), the paper's TN layout (Section 2.2.2)."""
+    name, a, b = wl.exact_family_for(shape, seed=5)
+    ref = orc.hgemm(a, b)
+    bt = np.ascontiguousarray(b.T)
+    assert np.array_equal(orc.hgemm(a, bt, b_col_major=True).view(np.uint16), ref.view(np.uint16))
+    for spec in all_mfma_specs() + all_mfma_specs(sk=2):
+        c, before, after, desc = run_hgemm(a, bt, spec=spec, b_col_major=True, guard=2)
+        assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all()
+
+
+def test_tn_default_plan_and_real_inputs():
+    shape = (260, 392, 712)
+    rng = np.random.default_rng(31)
+    a = wl.uniform_pm1(rng, shape[0], shape[2])
+    b = wl.uniform_pm1(rng, shape[2], shape[1])
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, np.ascontiguousarray(b.T), b_col_major=True)
+    assert desc.startswith("mfma")
+    assert_close(c, ref, "TN " + desc)
+
+
+@pytest.mark.parametrize("shape", [(300, 264, 200), (1024, 520, 328)])
+def test_pretransposed_b_option_bit_exact(shape):
+    name, a, b = wl.exact_family_for(shape, seed=6)
+    ref = orc.hgemm(a, b)
+    for spec in ("mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=2,sk=1,gm=8,tb=1", "mfma,bm=256,bn=256,bk=64,wm=2,wn=4,st=2,sk=2,gm=8,tb=1"):
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=2)
+        assert "tb=1" in desc
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all()
+
+
+@pytest.mark.parametrize("shape", [(1312, 1088, 512), (300, 264, 1000), (2100, 2050 // 8 * 8, 328)])
+def test_stream_k_bit_exact(shape):
+    """Stream-K: tiles that do not fill whole waves of 256 workgroups are shared by K-tile iterations."""
+    name, a, b = wl.exact_family_for(shape, seed=7)
+    ref = orc.hgemm(a, b)
+    ran = 0
+    for spec in all_mfma_specs():
+        spec = spec + ",sm=1"
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=2)
+        ran += "sm=1" in desc          # the plan drops sm when the tile count is a whole number of waves
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all()
+    assert ran > 0
+    bt = np.ascontiguousarray(b.T)
+    c, _, _, desc = run_hgemm(a, bt, spec="mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,sk=1,gm=8,sm=1", b_col_major=True)
+    assert_bit_exact(c, ref, f"TN {shape} {desc}")
+
+
+def test_stream_k_real_inputs_and_determinism():
+    shape = (1100, 1288, 2048)
+    rng = np.random.default_rng(41)
+    a = wl.uniform_pm1(rng, shape[0], shape[2])
+    b = wl.uniform_pm1(rng, shape[2], shape[1])
+    ref = orc.hgemm(a, b)
+    for spec in ("mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=2,sk=1,gm=8,sm=1", "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,sk=1,gm=0,sm=1",
+                 "mfma,bm=256,bn=256,bk=64,wm=2,wn=4,st=2,sk=1,gm=8,sm=1"):
+        c1, _, _, desc = run_hgemm(a, b, spec=spec)
+        c2, _, _, _ = run_hgemm(a, b, spec=spec)
+        assert "sm=1" in desc
+        assert_close(c1, ref, desc)
+        assert np.array_equal(c1.view(np.uint16), c2.view(np.uint16)), desc
+
+
 @pytest.mark.parametrize("sk", [2, 3, 5])
 def test_split_k_bit_exact_and_ordered(sk):
     shape = (96, 136, 1000)
