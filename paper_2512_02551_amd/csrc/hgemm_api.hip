@@ -15,70 +15,22 @@
 
 #include "hgemm_aux.hpp"
 #include "hgemm_mfma.hpp"
+#include "hgemm_registry.hpp"
 
 namespace hgemm {
 
 // ---------------------------------------------------------------------------
-// Kernel registry: every compiled MFMA specialisation.
+// Kernel registry: every compiled MFMA specialisation (hgemm_configs.inc), gathered from the
+// translation units that instantiate them.
 // ---------------------------------------------------------------------------
-struct MfmaEntry {
-    int bm, bn, bk, wm, wn, st;
-    int threads, lds_bytes;
-    void (*plain)(GemmArgs);
-    void (*splitk)(GemmArgs);
-    void (*plain_tn)(GemmArgs);
-    void (*splitk_tn)(GemmArgs);
-    void (*streamk)(GemmArgs);
-    void (*streamk_tn)(GemmArgs);
-    void (*fixup)(GemmArgs);
-};
-
-template <class C> static MfmaEntry make_entry()
-{
-    return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::THREADS, C::LDS_BYTES,
-                     mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
-                     mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
-                     mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
-                     streamk_fixup_kernel<C::BM, C::BN, C::BK>};
-}
-
-#define HGEMM_MFMA_CONFIGS(X)                                                                    \
-    X(256, 256, 64, 2, 2, 2)                                                                     \
-    X(256, 256, 32, 2, 2, 3)                                                                     \
-    X(256, 256, 32, 2, 2, 4)                                                                     \
-    X(256, 128, 64, 2, 2, 2)                                                                     \
-    X(256, 128, 64, 2, 2, 3)                                                                     \
-    X(128, 256, 64, 2, 2, 2)                                                                     \
-    X(128, 256, 64, 2, 2, 3)                                                                     \
-    X(128, 128, 64, 2, 2, 2)                                                                     \
-    X(128, 128, 64, 2, 2, 4)                                                                     \
-    X(128, 128, 32, 2, 2, 4)                                                                     \
-    X(128, 64, 64, 2, 2, 4)                                                                      \
-    X(64, 128, 64, 2, 2, 4)                                                                      \
-    X(64, 64, 64, 2, 2, 4)                                                                       \
-    X(64, 256, 64, 1, 4, 3)                                                                      \
-    X(32, 256, 64, 1, 4, 4)                                                                      \
-    X(32, 128, 64, 1, 4, 4)                                                                      \
-    X(32, 128, 128, 1, 4, 4)                                                                     \
-    X(256, 256, 64, 2, 4, 2)                                                                     \
-    X(256, 256, 64, 4, 2, 2)                                                                     \
-    X(256, 256, 32, 2, 4, 3)                                                                     \
-    X(256, 256, 32, 2, 4, 4)                                                                     \
-    X(256, 256, 32, 2, 4, 5)                                                                     \
-    X(256, 256, 32, 2, 2, 5)                                                                     \
-    X(256, 128, 64, 2, 4, 3)                                                                     \
-    X(128, 256, 64, 2, 4, 3)                                                                     \
-    X(256, 128, 64, 4, 2, 3)                                                                     \
-    X(256, 128, 32, 2, 4, 6)                                                                     \
-    X(128, 256, 32, 2, 4, 6)
-
 static const std::vector<MfmaEntry>& registry()
 {
-    static const std::vector<MfmaEntry> r = {
-#define X(bm, bn, bk, wm, wn, st) make_entry<MfmaCfg<bm, bn, bk, wm, wn, st>>(),
-        HGEMM_MFMA_CONFIGS(X)
-#undef X
-    };
+    static const std::vector<MfmaEntry> r = [] {
+        std::vector<MfmaEntry> v;
+        register_chunk_0(v); register_chunk_1(v); register_chunk_2(v); register_chunk_3(v);
+        register_chunk_4(v); register_chunk_5(v); register_chunk_6(v); register_chunk_7(v);
+        return v;
+    }();
     return r;
 }
 
@@ -87,6 +39,7 @@ enum Family { FAM_GENERIC = 0, FAM_MFMA = 1 };
 struct Spec {
     Family fam = FAM_GENERIC;
     int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0, st = 0;
+    int pf = 1;     // register prefetch distance in k-steps
     int sk = 1;     // split-K factor
     int gm = 8;     // tile-order group height; 0 = row-major
     int tb = 0;     // 1 = transpose row-major B into the workspace first, then run the K-contiguous (TN) kernel
@@ -97,8 +50,8 @@ static std::string spec_to_string(const Spec& s)
 {
     char buf[160];
     if (s.fam == FAM_GENERIC) return "generic";
-    snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
-             s.st, s.sk, s.gm, s.tb ? ",tb=1" : "");
+    snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,pf=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
+             s.st, s.pf, s.sk, s.gm, s.tb ? ",tb=1" : "");
     if (s.sm) strncat(buf, ",sm=1", sizeof buf - strlen(buf) - 1);
     return buf;
 }
@@ -133,6 +86,7 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "wm") sp.wm = (int)v;
         else if (key == "wn") sp.wn = (int)v;
         else if (key == "st") sp.st = (int)v;
+        else if (key == "pf") sp.pf = (int)v;
         else if (key == "sk") sp.sk = (int)v;
         else if (key == "gm") sp.gm = (int)v;
         else if (key == "tb") sp.tb = (int)v;
@@ -147,7 +101,7 @@ static bool parse_spec(const char* text, Spec* out)
 static const MfmaEntry* find_entry(const Spec& s)
 {
     for (const MfmaEntry& e : registry())
-        if (e.bm == s.bm && e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.st == s.st) return &e;
+        if (e.bm == s.bm && e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.st == s.st && e.pf == s.pf) return &e;
     return nullptr;
 }
 
@@ -161,7 +115,7 @@ struct hgemm_plan_s {
     Spec spec;
     const MfmaEntry* entry;     // null for the generic family
     GemmArgs args;              // pointers filled in at run time
-    void* workspace;            // [transposed B (when spec.tb)] [split-K partial sums]
+    void* workspace;            // [transposed B (when spec.tb)] [split-K / stream-K partial sums] [split-K counters]
     size_t workspace_bytes;
     size_t partial_offset;      // byte offset of the partial sums inside the workspace
     bool tn_kernel;             // the MFMA kernel reads B with K contiguous
@@ -296,8 +250,10 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     size_t bt_bytes = s.tb ? (((size_t)N * (size_t)K * 2 + 255) / 256) * 256 : 0;
     size_t partial_bytes = sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
     if (s.sm) partial_bytes = (size_t)2 * a.sk_workers * e->bm * e->bn * sizeof(float);
+    partial_bytes = ((partial_bytes + 255) / 256) * 256;
+    const size_t counter_bytes = sk > 1 ? (((size_t)a.tiles_m * a.tiles_n * sizeof(int) + 255) / 256) * 256 : 0;
     p->partial_offset = bt_bytes;
-    p->workspace_bytes = bt_bytes + partial_bytes;
+    p->workspace_bytes = bt_bytes + partial_bytes + counter_bytes;
     if (p->workspace_bytes) {
         if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
             (void)hipGetLastError();
@@ -306,6 +262,17 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
             return HGEMM_ERR_ALLOC;
         }
         if (partial_bytes) a.partial = (float*)((char*)p->workspace + bt_bytes);
+        if (counter_bytes) {
+            a.counters = (int*)((char*)p->workspace + bt_bytes + partial_bytes);
+            // the counters start at zero; every launch leaves them at zero again
+            if (hipMemset(a.counters, 0, counter_bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+                (void)hipGetLastError();
+                hipFree(p->workspace);
+                p->workspace = nullptr;
+                p->workspace_bytes = 0;
+                return HGEMM_ERR_ALLOC;
+            }
+        }
     }
     return HGEMM_OK;
 }
@@ -434,16 +401,11 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
         hipLaunchKernelGGL(plan->tn_kernel ? e->streamk_tn : e->streamk, dim3((unsigned)(a.dp_tiles + a.sk_workers)), dim3(e->threads),
                            e->lds_bytes, stream, a);
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
-        hipLaunchKernelGGL(e->fixup, dim3(wgs - (unsigned)a.dp_tiles), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(e->fixup, dim3(wgs - (unsigned)a.dp_tiles, (unsigned)((e->bm * e->bn / 4 + 1023) / 1024)), dim3(256), 0,
+                           stream, a);
     } else if (a.splits > 1) {
         hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_tn : e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes,
                            stream, a);
-        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
-        const int64_t quads = M * (N / 4);
-        const int blocks = (int)std::min<int64_t>((quads + 255) / 256, 2048);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
-                           (const float*)((const char*)plan->workspace + plan->partial_offset), (_Float16*)C, (int)M, (int)N,
-                           (int)plan->lay.ldc, a.splits);
     } else {
         hipLaunchKernelGGL(plan->tn_kernel ? e->plain_tn : e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     }
@@ -511,16 +473,17 @@ const char* hgemm_spec_help(void)
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1]\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
+            "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
             "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
             "    tb = 1: copy row-major B transposed into the workspace first and run the K-contiguous kernel,\n"
             "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
             "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
-            "    compiled (bm,bn,bk,wm,wn,st):";
+            "    compiled (bm,bn,bk,wm,wn,st,pf):";
         for (const MfmaEntry& e : registry()) {
             char b[64];
-            snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st);
+            snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
             t += b;
         }
         t += "\n";
@@ -558,7 +521,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
             }
             if (t % CUS != 0 && ktiles >= 4 && e.bm >= 64 && e.bn >= 64) {
                 Spec s;
-                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.sk = 1; s.gm = 8; s.sm = 1;
+                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = 1; s.gm = 8; s.sm = 1;
                 out += spec_to_string(s);
                 out += "\n";
             }
@@ -566,7 +529,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                 for (int gm : {8, 0, 4, 16}) {
                     if (gm != 8 && (t < 2 * CUS)) continue;      // order matters only when tiles outnumber CUs
                     Spec s;
-                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.sk = sk; s.gm = gm;
+                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
                     // row-major B, tall problem: paying one transposing copy of B can be cheaper than

@@ -38,6 +38,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace hgemm {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -52,7 +54,8 @@ struct GemmArgs {
     const _Float16* A;
     const _Float16* B;
     _Float16* C;
-    float* partial;      // split-K: [S][M][N] fp32, else unused
+    float* partial;      // split-K: [S][M][N] fp32; stream-K: partial tiles; else unused
+    int* counters;       // split-K: one arrival counter per output tile, zero between launches
     int M, N, K;
     int lda, ldb, ldc;   // elements
     int tiles_m, tiles_n;
@@ -104,9 +107,12 @@ __host__ __device__ inline int64_t tile_of_workgroup(int64_t wg, int64_t tiles_m
     return logical;
 }
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_>
+// PF = register prefetch distance in k-steps (Sections 5.3.1 and 5.3.2: PF = 1 is the
+// double-buffered ping-pong, PF = 3 the multi-step prefetch with four fragment sets).
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int PF_ = 1>
 struct MfmaCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int PF = PF_, NSLOT = PF_ + 1;
     static constexpr int NWAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = 64 * NWAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;       // wave tile
@@ -126,7 +132,8 @@ struct MfmaCfg {
     static constexpr int B_RPI = 64 / B_CPR;                           // B rows per wave-load (may be 0 if BN > 512)
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
-    static_assert(KS % 2 == 0, "fragment ping-pong needs an even number of k-steps");
+    static_assert(KS % NSLOT == 0, "the k-steps of a tile must cycle through the fragment sets a whole number of times");
+    static_assert(PF >= 1 && PF <= KS, "prefetch distance");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into wave loads");
     static_assert(BN >= 64 && BN <= 512, "BN");
     static_assert((NWAVES * A_RPI) % 16 == 0, "A swizzle must be periodic in the rows one round of loads covers");
@@ -293,8 +300,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int ft_swz = swz_a<C>(ft_row);
     const int ft_base = ft_row * (C::BK * 2);
 
-    half8 fa[2][C::TM];
-    half8 fb[2][C::TN];
+    half8 fa[C::NSLOT][C::TM];
+    half8 fb[C::NSLOT][C::TN];
     float16v acc[C::TM][C::TN];
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
@@ -340,14 +347,15 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     };
 
     // One k-step with a pinned instruction order: matrix-core instruction i is followed by its
-    // share of the side work (fragment reads of the next k-step, and in the last k-step of a
-    // tile the global->LDS copies of a later tile), so that the side work issues in the shadow of
-    // the matrix cores instead of in a burst in front of them (the staggered prefetch of
+    // share of the side work (fragment reads for the k-step PF steps ahead, and after the barrier
+    // of a tile the global->LDS copies of a later tile), so that the side work issues in the shadow
+    // of the matrix cores instead of in a burst in front of them (the staggered prefetch of
     // Section 5.3.4, taken to instruction granularity).
-    auto kstep = [&](int slot, int rbuf, int rks, bool do_reads, int dma_kt, int dma_buf, bool do_dma) {
+    // Copies [dma_lo, dma_hi) of tile dma_kt go to buffer dma_buf.
+    auto kstep = [&](int slot, int rbuf, int rks, int rslot, bool do_reads, int dma_kt, int dma_buf, int dma_lo, int dma_hi) {
         constexpr int NSIDE_MAX = NREADS + C::LOADS;
-        const int nside = (do_reads ? NREADS : 0) + (do_dma ? C::LOADS : 0);
-        (void)NSIDE_MAX;
+        const int nreads = do_reads ? NREADS : 0;
+        const int nside = nreads + (dma_hi - dma_lo);
 #pragma unroll
         for (int i = 0; i < NMMA; ++i) {
             mma_one(slot, i);
@@ -357,19 +365,44 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             for (int t = 0; t < NSIDE_MAX; ++t) {
                 if (t >= lo && t < hi) {
                     // fragment reads first (they are needed soonest), then the copies
-                    if (do_reads && t < NREADS) read_one(rbuf, rks, slot ^ 1, t);
-                    else dma_one(dma_kt, dma_buf, t - (do_reads ? NREADS : 0));
+                    if (t < nreads) read_one(rbuf, rks, rslot, t);
+                    else dma_one(dma_kt, dma_buf, dma_lo + t - nreads);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
+    // One K-tile.  Tile kt lives in LDS buffer kt % STAGES.  The k-step that runs at position ks
+    // reads the fragments of position ks + PF; the barrier sits in front of the first k-step whose
+    // reads fall into the next tile (ks == KS - PF): by then every wave holds all its fragments of
+    // tile kt in registers, so after the barrier buffer kt % STAGES is free for tile kt+STAGES, and
+    // tile kt+1 (copies issued STAGES-1 tiles earlier) is complete and visible to all waves.
+    // WAIT = number of copies that may still be in flight at the barrier; HAS_NEXT = a next tile
+    // exists; DMA = a tile kt+STAGES exists and is copied after the barrier.
+    auto tile_body = [&](int kt, int buf, int nbuf, auto wait_tag, auto has_next_tag, auto dma_tag) {
+        constexpr int WAIT = decltype(wait_tag)::value;
+        constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+        constexpr bool DMA = decltype(dma_tag)::value;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const bool after = ks >= C::KS - C::PF;            // this step runs behind the barrier
+            if (ks == C::KS - C::PF && HAS_NEXT) {
+                wait_vmcnt<WAIT>();
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            }
+            const int t = ks + C::PF;
+            const bool in_next = t >= C::KS;
+            const int j = ks - (C::KS - C::PF);                 // index among the post-barrier steps
+            const int dlo = (DMA && after) ? (j * C::LOADS) / C::PF : 0;
+            const int dhi = (DMA && after) ? ((j + 1) * C::LOADS) / C::PF : 0;
+            kstep(ks % C::NSLOT, in_next ? nbuf : buf, in_next ? t - C::KS : t, t % C::NSLOT, in_next ? HAS_NEXT : true,
+                  kt + C::STAGES, buf, dlo, dhi);
+        }
+    };
+    using std::integral_constant;
+
     // ---- main loop ----------------------------------------------------------
-    // Tile kt lives in LDS buffer kt % STAGES.  In iteration kt the barrier sits in front of the
-    // last k-step: by then every wave holds its last fragments of tile kt in registers, so after
-    // the barrier buffer kt % STAGES is free for tile kt+STAGES, and tile kt+1 (copies issued
-    // STAGES-1 iterations earlier) is complete and visible to all waves.
     if (KT > 0) {
 #pragma unroll
         for (int s = 0; s < C::STAGES; ++s)
@@ -377,7 +410,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         // tile 0 must have landed: at most the later prologue tiles may still be in flight
         if (KT >= C::STAGES) wait_vmcnt<(C::STAGES - 1) * C::LOADS>(); else wait_vmcnt<0>();
         asm volatile("s_barrier" ::: "memory");
-        read_frags(0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < C::PF; ++ks) read_frags(0, ks, ks);
         __builtin_amdgcn_sched_barrier(0);
 
         int buf = 0;
@@ -385,27 +419,18 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         // steady state: a later tile exists to be copied and a next tile exists to be read
         for (; kt + C::STAGES < KT; ++kt) {
             const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-#pragma unroll
-            for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
-            wait_vmcnt<(C::STAGES - 2) * C::LOADS>();
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            kstep((C::KS - 1) & 1, nbuf, 0, true, kt + C::STAGES, buf, true);
+            tile_body(kt, buf, nbuf, integral_constant<int, (C::STAGES - 2) * C::LOADS>{}, integral_constant<bool, true>{},
+                      integral_constant<bool, true>{});
             buf = nbuf;
         }
         // drain: no more copies to issue
         for (; kt + 1 < KT; ++kt) {
             const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-#pragma unroll
-            for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
-            wait_vmcnt<0>();
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            kstep((C::KS - 1) & 1, nbuf, 0, true, 0, 0, false);
+            tile_body(kt, buf, nbuf, integral_constant<int, 0>{}, integral_constant<bool, true>{}, integral_constant<bool, false>{});
             buf = nbuf;
         }
         // last tile
-#pragma unroll
-        for (int ks = 0; ks < C::KS - 1; ++ks) kstep(ks & 1, buf, ks + 1, true, 0, 0, false);
-        kstep((C::KS - 1) & 1, 0, 0, false, 0, 0, false);
+        tile_body(kt, buf, buf, integral_constant<int, 0>{}, integral_constant<bool, false>{}, integral_constant<bool, false>{});
     }
 
     // ---- epilogue: fp32 -> fp16 (round to nearest even), 8-byte stores -------
@@ -446,6 +471,37 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
         }
     }
+    if (SPLITK) {
+        // Fused split-K reduction without a second launch and without waiting: every split stores
+        // its fp32 partial tile, then counts itself in; the workgroup that arrives last (whichever it
+        // is) sums the S partial tiles in split order 0..S-1 -- the same order every run, so the
+        // result is reproducible bit for bit -- rounds once and stores C.  Nobody spins.
+        __threadfence();                                   // partial tile visible device-wide before the count
+        __syncthreads();
+        int* flag = (int*)lds;
+        if (threadIdx.x == 0) {
+            const int arrived = atomicAdd(&g.counters[tile], 1);
+            const int last = arrived == g.splits - 1;
+            if (last) atomicExch(&g.counters[tile], 0);    // leave the counter clean for the next launch
+            *flag = last;
+        }
+        __syncthreads();
+        if (*flag) {
+            __threadfence();                               // see the other splits' partial tiles
+            const size_t plane = (size_t)g.M * g.N;
+            for (int q = threadIdx.x; q < C::BM * C::BN / 4; q += C::THREADS) {
+                const int m = m0 + q / (C::BN / 4), n = n0 + (q % (C::BN / 4)) * 4;
+                if (m >= g.M || n >= g.N) continue;
+                const float* p = g.partial + (size_t)m * g.N + n;
+                float4v sum = *(const float4v*)p;
+                for (int sp = 1; sp < g.splits; ++sp) sum += *(const float4v*)(p + sp * plane);
+                half4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
+                *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
+            }
+        }
+    }
     if (!(STREAMK && sk_worker) || sk_iter >= sk_end) break;
     first_segment = false;
     // the next segment's copies reuse the LDS buffers: every wave must be done reading them
@@ -453,7 +509,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
   }
 }
 
-// Stream-K second pass: one workgroup per tile that stream-K workers shared.  Sums the fp32
+// Stream-K second pass: grid.x = tiles that stream-K workers shared, grid.y = slices of a tile.  Sums the fp32
 // partial tiles of the workers that touched the tile, in increasing k (= increasing worker)
 // order, rounds once to fp16 and stores the in-range part of the tile.
 template <int BM, int BN, int BK>
@@ -472,7 +528,8 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmArgs g)
     const int tile = (int)tile_of_workgroup(g.dp_tiles + t, g.tiles_m, g.tiles_n, g.swizzle);
     const int m0 = (tile / g.tiles_n) * BM;
     const int n0 = (tile % g.tiles_n) * BN;
-    for (int q = threadIdx.x; q < BM * BN / 4; q += 256) {
+    // blockIdx.y picks a slice of 1024 groups of 4 consecutive columns
+    for (int q = blockIdx.y * 1024 + threadIdx.x; q < min((int)(blockIdx.y + 1) * 1024, BM * BN / 4); q += 256) {
         const int r = q / (BN / 4), c = (q % (BN / 4)) * 4;
         if (m0 + r >= g.M || n0 + c >= g.N) continue;
         float4v sum = {0.f, 0.f, 0.f, 0.f};

@@ -1,0 +1,40 @@
+// Registry of compiled MFMA specialisations, filled by one function per translation unit.
+#pragma once
+#include <vector>
+
+#include "hgemm_mfma.hpp"
+
+namespace hgemm {
+
+struct MfmaEntry {
+    int bm, bn, bk, wm, wn, st, pf;
+    int threads, lds_bytes;
+    void (*plain)(GemmArgs);
+    void (*splitk)(GemmArgs);
+    void (*plain_tn)(GemmArgs);
+    void (*splitk_tn)(GemmArgs);
+    void (*streamk)(GemmArgs);
+    void (*streamk_tn)(GemmArgs);
+    void (*fixup)(GemmArgs);
+};
+
+template <class C> inline MfmaEntry make_entry()
+{
+    return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::PF, C::THREADS, C::LDS_BYTES,
+                     mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
+                     mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
+                     mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
+                     streamk_fixup_kernel<C::BM, C::BN, C::BK>};
+}
+
+void register_chunk(int chunk, std::vector<MfmaEntry>& out);    // defined in hgemm_api.hip
+void register_chunk_0(std::vector<MfmaEntry>& out);
+void register_chunk_1(std::vector<MfmaEntry>& out);
+void register_chunk_2(std::vector<MfmaEntry>& out);
+void register_chunk_3(std::vector<MfmaEntry>& out);
+void register_chunk_4(std::vector<MfmaEntry>& out);
+void register_chunk_5(std::vector<MfmaEntry>& out);
+void register_chunk_6(std::vector<MfmaEntry>& out);
+void register_chunk_7(std::vector<MfmaEntry>& out);
+
+}  // namespace hgemm

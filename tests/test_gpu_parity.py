@@ -19,8 +19,8 @@ def all_mfma_specs(sk=1, gm=8):
     for line in hg.spec_help().splitlines():
         if "compiled" in line:
             for tup in line.split(":")[1].split():
-                bm, bn, bk, wm, wn, st = (int(x) for x in tup.strip("()").split(","))
-                out.append(f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},sk={sk},gm={gm}")
+                bm, bn, bk, wm, wn, st, pf = (int(x) for x in tup.strip("()").split(","))
+                out.append(f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},pf={pf},sk={sk},gm={gm}")
     assert out
     return out
 
