@@ -86,8 +86,9 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
  *               takes the generic kernel.  C is write-only: every element is
  *               overwritten (beta = 0), earlier contents never leak.
  *   hip_stream  a hipStream_t passed as void*; NULL = the default stream.
- * Asynchronous; allocates nothing; all kernels (main, stream-K fix-up, the
- * optional transposing copy of B) go to hip_stream in order.
+ * Asynchronous; allocates nothing; all kernels (main, split-K reduction,
+ * stream-K fix-up, the optional transposing copy of B) go to hip_stream in
+ * order.
  * Errors: INVALID_ARG (null plan / null pointer with a non-empty problem),
  * LAUNCH.
  */

@@ -115,7 +115,7 @@ struct hgemm_plan_s {
     Spec spec;
     const MfmaEntry* entry;     // null for the generic family
     GemmArgs args;              // pointers filled in at run time
-    void* workspace;            // [transposed B (when spec.tb)] [split-K / stream-K partial sums] [split-K counters]
+    void* workspace;            // [transposed B (when spec.tb)] [split-K / stream-K partial sums]
     size_t workspace_bytes;
     size_t partial_offset;      // byte offset of the partial sums inside the workspace
     bool tn_kernel;             // the MFMA kernel reads B with K contiguous
@@ -251,9 +251,8 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     size_t partial_bytes = sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
     if (s.sm) partial_bytes = (size_t)2 * a.sk_workers * e->bm * e->bn * sizeof(float);
     partial_bytes = ((partial_bytes + 255) / 256) * 256;
-    const size_t counter_bytes = sk > 1 ? (((size_t)a.tiles_m * a.tiles_n * sizeof(int) + 255) / 256) * 256 : 0;
     p->partial_offset = bt_bytes;
-    p->workspace_bytes = bt_bytes + partial_bytes + counter_bytes;
+    p->workspace_bytes = bt_bytes + partial_bytes;
     if (p->workspace_bytes) {
         if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
             (void)hipGetLastError();
@@ -262,17 +261,6 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
             return HGEMM_ERR_ALLOC;
         }
         if (partial_bytes) a.partial = (float*)((char*)p->workspace + bt_bytes);
-        if (counter_bytes) {
-            a.counters = (int*)((char*)p->workspace + bt_bytes + partial_bytes);
-            // the counters start at zero; every launch leaves them at zero again
-            if (hipMemset(a.counters, 0, counter_bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-                (void)hipGetLastError();
-                hipFree(p->workspace);
-                p->workspace = nullptr;
-                p->workspace_bytes = 0;
-                return HGEMM_ERR_ALLOC;
-            }
-        }
     }
     return HGEMM_OK;
 }
@@ -406,6 +394,12 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     } else if (a.splits > 1) {
         hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_tn : e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes,
                            stream, a);
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        const int64_t quads = M * (N / 4);
+        const int blocks = (int)std::min<int64_t>((quads + 255) / 256, 2048);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                           (const float*)((const char*)plan->workspace + plan->partial_offset), (_Float16*)C, (int)M, (int)N,
+                           (int)plan->lay.ldc, a.splits);
     } else {
         hipLaunchKernelGGL(plan->tn_kernel ? e->plain_tn : e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     }

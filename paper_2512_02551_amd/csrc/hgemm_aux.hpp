@@ -1,4 +1,4 @@
-// Auxiliary kernels: the generic any-shape GEMM, a transposing copy, a fill
+// Auxiliary kernels: the generic any-shape GEMM, the split-K reduction, a transposing copy, a fill
 // kernel, and the two roofline calibration kernels.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -24,6 +24,36 @@ __global__ __launch_bounds__(256) void generic_gemm_kernel(const _Float16* __res
         for (int64_t k = 0; k < K; ++k) acc += (float)A[m * lda + k] * (float)B[k * ldb + n];
     }
     C[m * ldc + n] = (_Float16)acc;
+}
+
+// Split-K second pass: C[m][n] = fp16( partial[0][m][n] + partial[1][m][n] + ... ) summed in
+// split order, so the result does not depend on which workgroup finished first.  A separate
+// launch on purpose: a reduction fused into the main kernel behind device-scope fences (last
+// arriving workgroup sums) was measured slower -- every workgroup's release fence writes back
+// its XCD's L2 -- than the few microseconds of a second launch.
+// One thread handles 4 consecutive n.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, _Float16* __restrict__ C,
+                                                            int M, int N, int ldc, int splits)
+{
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const int64_t quads_per_row = N / 4;
+    const int64_t total = (int64_t)M * quads_per_row;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t plane = (int64_t)M * N;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t m = t / quads_per_row, n = (t % quads_per_row) * 4;
+        const float* p = partial + m * N + n;
+        float4v s = *(const float4v*)p;
+        for (int sp = 1; sp < splits; ++sp) {
+            const float4v v = *(const float4v*)(p + sp * plane);
+            s += v;
+        }
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (_Float16)s[e];
+        *(half4*)(C + m * ldc + n) = o;
+    }
 }
 
 // out (N x K, row-major, packed) = transpose of in (K x N, row-major, leading dimension ld).

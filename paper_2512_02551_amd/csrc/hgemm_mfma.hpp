@@ -55,7 +55,6 @@ struct GemmArgs {
     const _Float16* B;
     _Float16* C;
     float* partial;      // split-K: [S][M][N] fp32; stream-K: partial tiles; else unused
-    int* counters;       // split-K: one arrival counter per output tile, zero between launches
     int M, N, K;
     int lda, ldb, ldc;   // elements
     int tiles_m, tiles_n;
@@ -433,72 +432,69 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         tile_body(kt, buf, buf, integral_constant<int, 0>{}, integral_constant<bool, false>{}, integral_constant<bool, false>{});
     }
 
-    // ---- epilogue: fp32 -> fp16 (round to nearest even), 8-byte stores -------
+    // ---- epilogue ------------------------------------------------------------
     // acc[tm][tn][v]: row m = m0 + wm*WTM + tm*32 + l%32, columns n = n0 + wn*WTN + tn*32 + 8*(v/4) + 4*(l/32) + v%4
     const int row_t = wm * C::WTM + (lane & 31);           // tile-local
     const int col_t = wn * C::WTN + 4 * (lane >> 5);
-    float* sk_slot = nullptr;
-    if (STREAMK && to_partial)
-        sk_slot = g.partial + ((size_t)2 * ((int)blockIdx.x - g.dp_tiles) + (first_segment ? 0 : 1)) * (size_t)(C::BM * C::BN);
+    if (!to_partial) {
+        // fp32 -> fp16 (round to nearest even), then through LDS so that a lane stores 16 contiguous
+        // bytes and a wave whole row segments (Section 5.3.3: registers -> shared -> global with wide
+        // copies).  Each wave turns its own 32 x WTN slab in a private LDS region, one slab per tm.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // all waves are done with the operand buffers
+        constexpr int ROWB = C::WTN * 2 + 8;      // +8 bytes: the 32 rows a half-wave writes hit 32 different banks pairs
+        constexpr int CPR = C::WTN / 8;           // 16-byte chunks per slab row
+        char* stage = lds + wave * (32 * ROWB);
+        static_assert(C::NWAVES * 32 * ROWB <= C::LDS_BYTES, "epilogue staging must fit in the operand buffers");
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) {
-        const int m = m0 + row_t + tm * 32;
-        if (m < g.M || (STREAMK && to_partial)) {
+        for (int tm = 0; tm < C::TM; ++tm) {
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn) {
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    half4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[tm][tn][vg * 4 + e];
+                    *(half4*)(stage + (lane & 31) * ROWB + (tn * 32 + vg * 8 + 4 * (lane >> 5)) * 2) = o;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < (32 * CPR) / 64; ++j) {
+                const int idx = j * 64 + lane;
+                const int r = idx / CPR, ch = idx % CPR;
+                const half4 lo = *(const half4*)(stage + r * ROWB + ch * 16);
+                const half4 hi = *(const half4*)(stage + r * ROWB + ch * 16 + 8);
+                const int m = m0 + wm * C::WTM + tm * 32 + r;
+                const int n = n0 + wn * C::WTN + ch * 8;
+                if (m < g.M && n < g.N) {
+                    half8 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+                    *(half8*)(g.C + (size_t)m * g.ldc + n) = v;
+                }
+            }
+        }
+    } else {
+        // fp32 partial sums (split-K plane or stream-K partial tile): 16-byte stores straight from registers
+        float* sk_slot = nullptr;
+        if (STREAMK)
+            sk_slot = g.partial + ((size_t)2 * ((int)blockIdx.x - g.dp_tiles) + (first_segment ? 0 : 1)) * (size_t)(C::BM * C::BN);
+#pragma unroll
+        for (int tm = 0; tm < C::TM; ++tm) {
+            const int m = m0 + row_t + tm * 32;
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn) {
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg) {
                     const int n = n0 + col_t + tn * 32 + vg * 8;
-                    if (STREAMK && to_partial) {
-                        float4v o;
+                    float4v o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
+                    for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
+                    if (STREAMK) {
                         *(float4v*)(sk_slot + (row_t + tm * 32) * C::BN + col_t + tn * 32 + vg * 8) = o;
-                    } else if (n < g.N) {
-                        if (SPLITK) {
-                            float4v o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
-                            *(float4v*)(g.partial + ((size_t)split * g.M + m) * g.N + n) = o;
-                        } else {
-                            half4 o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[tm][tn][vg * 4 + e];
-                            *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
-                        }
+                    } else if (m < g.M && n < g.N) {
+                        *(float4v*)(g.partial + ((size_t)split * g.M + m) * g.N + n) = o;
                     }
                 }
-            }
-        }
-    }
-    if (SPLITK) {
-        // Fused split-K reduction without a second launch and without waiting: every split stores
-        // its fp32 partial tile, then counts itself in; the workgroup that arrives last (whichever it
-        // is) sums the S partial tiles in split order 0..S-1 -- the same order every run, so the
-        // result is reproducible bit for bit -- rounds once and stores C.  Nobody spins.
-        __threadfence();                                   // partial tile visible device-wide before the count
-        __syncthreads();
-        int* flag = (int*)lds;
-        if (threadIdx.x == 0) {
-            const int arrived = atomicAdd(&g.counters[tile], 1);
-            const int last = arrived == g.splits - 1;
-            if (last) atomicExch(&g.counters[tile], 0);    // leave the counter clean for the next launch
-            *flag = last;
-        }
-        __syncthreads();
-        if (*flag) {
-            __threadfence();                               // see the other splits' partial tiles
-            const size_t plane = (size_t)g.M * g.N;
-            for (int q = threadIdx.x; q < C::BM * C::BN / 4; q += C::THREADS) {
-                const int m = m0 + q / (C::BN / 4), n = n0 + (q % (C::BN / 4)) * 4;
-                if (m >= g.M || n >= g.N) continue;
-                const float* p = g.partial + (size_t)m * g.N + n;
-                float4v sum = *(const float4v*)p;
-                for (int sp = 1; sp < g.splits; ++sp) sum += *(const float4v*)(p + sp * plane);
-                half4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
-                *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
             }
         }
     }
