@@ -6,9 +6,10 @@
 A step is one pass of the whole hot path (plan lookup done beforehand, then hgemm_run for
 every shape of the workload) over inputs that already sit in HBM.  The default workload is
 the square sweep M=N=K in {1024, 2048, 4096, 8192} with entries N(0,1)/sqrt(K).  After W
-untimed steps, exactly K steps are timed between device synchronisations; every hgemm_run
-is also bracketed by events on the stream it is launched on, which gives the per-shape
-times the metric is built from.  The last line printed is one JSON object:
+untimed steps, exactly K steps are timed between device synchronisations.  The K steps run
+shape-major (each shape's K calls back to back, bracketed by one pair of events on the stream
+they are launched on), which gives the per-shape times the metric is built from.  The last
+line printed is one JSON object:
 
   value        geometric mean over the workload's shapes of 2*M*N*K / (mean time per call), TFLOP/s
   roofline     the dominant kernel (largest share of the step) against the published MI355X peak
@@ -49,6 +50,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spec", default=None, help="force one specialisation for every shape (tuning aid)")
     ap.add_argument("--table", action="store_true", help="print the per-shape table to stderr")
+    ap.add_argument("--per-call-events", action="store_true",
+                    help="bracket every call with its own event pair (adds the event/launch gap to every call)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the roofline calibration kernels (MFMA-only loop, 1 GiB streaming read, "
                          "128 MiB fill) -- kernels of known size for scaling profiler counters")
@@ -76,21 +79,23 @@ def cpu_baseline():
     import workloads as wl
     from oracle import hgemm_oracle as orc
 
-    rows = 1024
+    rows = 2048
     a1, b1 = wl.c2_inputs((1024, 1024, 1024))
     a2, b2 = wl.c2_inputs((2048, 2048, 2048))
-    a2 = np.ascontiguousarray(a2[:rows])
+    a3, b3 = wl.c2_inputs((4096, 4096, 4096))
+    a3 = np.ascontiguousarray(a3[:rows])
     t0 = time.perf_counter()
     orc.hgemm(a1, b1)
     orc.hgemm(a2, b2)
+    orc.hgemm(a3, b3)
     dt = time.perf_counter() - t0
-    flop = 2.0 * 1024 ** 3 + 2.0 * rows * 2048 * 2048
+    flop = 2.0 * 1024 ** 3 + 2.0 * 2048 ** 3 + 2.0 * rows * 4096 * 4096
     return {
         "value": flop / dt * 1e-12,
         "unit": "TFLOP/s",
         "cores": orc.threads(),
         "kind": "oracle",
-        "sample": "oracle on the full 1024^3 product plus the first 1024 rows of the 2048^3 product "
+        "sample": "oracle on the full 1024^3 and 2048^3 products plus the first 2048 rows of the 4096^3 product "
                   f"of the square sweep ({dt:.1f} s of CPU work)",
     }
 
@@ -139,40 +144,50 @@ def main():
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
-    def one_step(step_idx, events=None):
-        for si, s in enumerate(sets):
-            a, b, c = s["bufs"][step_idx % len(s["bufs"])]
+    # Timed region.  The K steps are run shape-major: every shape's K calls go back to back on the
+    # stream between one pair of events (the paper's offline mode, Section 2.4.2: kernels executed
+    # consecutively without pauses), so a per-call time is that pair's elapsed time / K and carries no
+    # event or launch gap.  With --cold the K calls rotate through operand sets whose total exceeds the
+    # last-level cache.  "--per-call-events" brackets every single call instead.
+    def run_shape(s, k0, count, events=None):
+        for k in range(count):
+            a, b, c = s["bufs"][(k0 + k) % len(s["bufs"])]
             if events is not None:
-                e0, e1 = events[si]
-                e0.record(stream)
-                s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
-                e1.record(stream)
-            else:
-                s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+                events[k][0].record(stream)
+            s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+            if events is not None:
+                events[k][1].record(stream)
 
-    for w in range(args.warmup):
-        one_step(w)
+    for s in sets:
+        run_shape(s, 0, args.warmup)
     torch.cuda.synchronize()
 
-    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sets]
-                  for _ in range(args.steps)]
+    pair = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sets]
+    per_call = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+                for _ in sets] if args.per_call_events else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(args.steps):
-        one_step(args.warmup + k, all_events[k])
+    for si, s in enumerate(sets):
+        pair[si][0].record(stream)
+        run_shape(s, args.warmup, args.steps, per_call[si] if per_call else None)
+        pair[si][1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
     per_shape = []
     for si, s in enumerate(sets):
-        ts = np.array([all_events[k][si][0].elapsed_time(all_events[k][si][1]) for k in range(args.steps)])
         M, N, K = s["shape"]
         flop = 2.0 * M * N * K
         byts = 2.0 * (M * K + K * N + M * N)
-        mean_ms = float(ts.mean())
+        if per_call:
+            ts = np.array([e0.elapsed_time(e1) for (e0, e1) in per_call[si]])
+            mean_ms, med_ms, min_ms = float(ts.mean()), float(np.median(ts)), float(ts.min())
+        else:
+            mean_ms = pair[si][0].elapsed_time(pair[si][1]) / args.steps
+            med_ms = min_ms = mean_ms
         per_shape.append({
             "shape": [M, N, K], "spec": s["desc"], "workgroups": s["info"]["workgroups"],
-            "mean_us": mean_ms * 1e3, "median_us": float(np.median(ts)) * 1e3, "min_us": float(ts.min()) * 1e3,
+            "mean_us": mean_ms * 1e3, "median_us": med_ms * 1e3, "min_us": min_ms * 1e3,
             "tflops": flop / mean_ms * 1e-9, "gbs": byts / mean_ms * 1e-6,
             "frac_mfma_peak": flop / mean_ms * 1e-9 / PEAK_FP16_TFLOPS,
             "frac_hbm_peak": byts / mean_ms * 1e-6 / PEAK_HBM_GBS,
@@ -221,6 +236,7 @@ def main():
                          "C4": "200-shape grid from {64..12288}^3, uniform[-1,1]",
                          "C5": "16384x16384x{8192,16384}, uniform[-1,1]"}[args.workload],
             "layout": "NN row-major", "cache": "cold" if args.cold else "warm",
+            "timing": "per-call events" if args.per_call_events else "K back-to-back calls per shape between one event pair",
             "aggregate_tflops": total_flop * args.steps / wall * 1e-12,
         },
         "roofline": roofline,

@@ -53,7 +53,15 @@ def load() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2512_02551_amd.build` "
                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+    # PyTorch ships its own copy of the HIP runtime.  Device pointers and streams handed to this
+    # library come from torch, so both must sit on ONE runtime: import torch first, then the dynamic
+    # loader binds libhgemm.so to the runtime that is already in the process.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
+    _check_single_hip_runtime()
     i64, vp, ci, cp = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_char_p
     lp = ctypes.POINTER(Layouts)
     lib.hgemm_plan.restype = ci
@@ -88,6 +96,17 @@ def load() -> ctypes.CDLL:
     lib.hgemm_calibrate_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
     _lib = lib
     return lib
+
+
+def _check_single_hip_runtime() -> None:
+    try:
+        with open("/proc/self/maps") as f:
+            paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+    except OSError:
+        return
+    if len(paths) > 1:
+        raise ImportError("two HIP runtimes are loaded in this process (" + ", ".join(sorted(paths)) +
+                          "): import torch before loading libhgemm.so so that they share one")
 
 
 def status_string(status: int) -> str:
