@@ -35,9 +35,15 @@ if ROOT not in sys.path:
 PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per launch of the dominant kernel of the default workload (8192^3), from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per launch between the L2s and the memory side (last-level cache + HBM) for the kernels of the
+# default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by kernels of known size
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); figures and commands in profiles/mfma_gemm_kernel__square_sweep.md.
+MEASURED_TRAFFIC_BYTES = {
+    (1024, 1024, 1024): (2.0 * 6185.5 + 2048.0) * 1024,
+    (2048, 2048, 2048): (2.0 * 24648.4 + 8192.0) * 1024,
+    (4096, 4096, 4096): (2.0 * 98382.1 + 32768.0) * 1024,
+    (8192, 8192, 8192): (2.0 * 789658.9 + 131072.0) * 1024,
+}
 
 
 def parse_args():
