@@ -1,0 +1,95 @@
+"""GPU parity at the benchmark's full sizes, with the plans bench.py times (dispatch table / rules):
+sampled outputs evaluated one by one by the oracle, and full comparison where the oracle finishes in seconds."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2512_02551_amd as hg  # noqa: E402
+import workloads as wl  # noqa: E402
+from oracle import hgemm_oracle as orc  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import TOL, assert_bit_exact, assert_close, run_hgemm  # noqa: E402
+
+
+def _check_sampled(a, b, c, count, what):
+    ii, jj = wl.sample_positions((a.shape[0], b.shape[1], a.shape[1]), count)
+    ref = orc.hgemm_at(a, b, ii, jj).astype(np.float64)
+    got = c[ii, jj].astype(np.float64)
+    assert not np.isnan(got).any(), what
+    err = np.abs(got - ref)
+    bound = TOL * np.maximum(1.0, np.abs(ref))
+    assert (err <= bound).all(), f"{what}: worst {float((err / bound).max()):.3g}x the bound"
+    return float((err / bound).max())
+
+
+def test_c1_single_256_cubed_full():
+    a, b = wl.c1_inputs()
+    c, _, _, desc = run_hgemm(a, b)
+    assert_close(c, orc.hgemm(a, b), "C1 " + desc)
+
+
+@pytest.mark.parametrize("shape", wl.C2_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_c2_square_sweep(shape):
+    a, b = wl.c2_inputs(shape)
+    c, _, _, desc = run_hgemm(a, b)
+    if shape[0] <= 1024:
+        assert_close(c, orc.hgemm(a, b), f"C2 {shape} {desc}")
+    else:
+        worst = _check_sampled(a, b, c, 4000, f"C2 {shape} {desc}")
+        print(f"C2 {shape} [{desc}] worst error {worst:.3g} of the bound")
+
+
+@pytest.mark.parametrize("shape", [s for s in wl.C3_SHAPES if s[0] in (1, 16, 128, 512) and s[1:] in ((11008, 4096), (4096, 11008), (14336, 4096))]
+                         + [(1, 4096, 4096), (64, 4096, 4096)], ids=lambda s: "x".join(map(str, s)))
+def test_c3_llm_skinny_shapes(shape):
+    a, b = wl.c3_inputs(shape)
+    c, before, after, desc = run_hgemm(a, b, guard=1)
+    _check_sampled(a, b, c, 3000, f"C3 {shape} {desc}")
+    assert np.isnan(before).all() and np.isnan(after).all()
+
+
+def test_c3_small_m_full_rows():
+    # M = 1 and M = 16 against the full oracle product on a narrower N (the oracle's cost is M*N*K)
+    for shape in [(1, 4096, 4096), (16, 4096, 4096)]:
+        a, b = wl.c3_inputs(shape)
+        c, _, _, desc = run_hgemm(a, b)
+        assert_close(c, orc.hgemm(a, b), f"C3 {shape} {desc}")
+
+
+@pytest.mark.parametrize("shape", [(64, 64, 64), (64, 12288, 64), (12288, 64, 12288), (2048, 128, 8192), (512, 12288, 64),
+                                   (128, 256, 4096), (4096, 4096, 256), (12288, 2048, 8192), (2048, 512, 12288)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_c4_grid_shapes(shape):
+    a, b = wl.c4_inputs(shape)
+    c, _, _, desc = run_hgemm(a, b)
+    _check_sampled(a, b, c, 3000, f"C4 {shape} {desc}")
+    # and the exact-integer family of the same shape, sampled positions compared bit for bit
+    name, ai, bi = wl.exact_family_for(shape, seed=11)
+    ci, _, _, _ = run_hgemm(ai, bi)
+    ii, jj = wl.sample_positions(shape, 3000, seed=1)
+    ref = orc.hgemm_at(ai, bi, ii, jj)
+    got = ci[ii, jj]
+    sel = np.abs(ref.astype(np.float64)) <= 2048
+    assert sel.mean() > 0.5
+    assert np.array_equal(got[sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {name} {desc}"
+
+
+def test_c5_small_integer_16384_full_bit_exact():
+    shape = wl.C5_INT_SHAPE
+    a, b = wl.small_int_inputs(shape, seed=0)
+    ref = orc.hgemm(a, b)                      # 3.4e10 multiply-adds, seconds on the machine's cores
+    c, _, _, desc = run_hgemm(a, b)
+    assert np.abs(ref.astype(np.float64)).max() <= 2048
+    assert_bit_exact(c, ref, f"C5 integer {desc}")
+
+
+def test_c5_large_16384_k8192_sampled():
+    shape = wl.C5_SHAPES[0]
+    a, b = wl.c5_inputs(shape)
+    c, _, _, desc = run_hgemm(a, b)
+    worst = _check_sampled(a, b, c, 3000, f"C5 {shape} {desc}")
+    print(f"C5 {shape} [{desc}] worst error {worst:.3g} of the bound")
