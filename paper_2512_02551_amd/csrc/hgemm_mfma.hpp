@@ -160,9 +160,10 @@ __device__ inline int4v make_rsrc(const void* base, unsigned bytes)
 {
     const uint64_t a = (uint64_t)base;
     int4v r;
-    r[0] = (int)(uint32_t)a;
-    r[1] = (int)(uint32_t)((a >> 32) & 0xffffu);
-    r[2] = (int)bytes;
+    // the descriptor lives in scalar registers: say so, whatever the optimiser thinks of its inputs
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
     r[3] = 0x00020000;
     return r;
 }
@@ -175,7 +176,7 @@ __device__ inline void dma16(int4v rsrc, unsigned lds_addr, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc)
                  : "memory");
 }
 
