@@ -44,10 +44,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
         const int64_t m = t / quads_per_row, n = (t % quads_per_row) * 4;
         const float* p = partial + m * N + n;
-        float4v s = *(const float4v*)p;
-        for (int sp = 1; sp < splits; ++sp) {
-            const float4v v = *(const float4v*)(p + sp * plane);
-            s += v;
+        float4v s = {0.f, 0.f, 0.f, 0.f};
+        // eight independent loads in flight at a time; the additions stay in split order
+        for (int sp0 = 0; sp0 < splits; sp0 += 8) {
+            float4v v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = float4v{0.f, 0.f, 0.f, 0.f};
+                if (sp0 + u < splits) v[u] = *(const float4v*)(p + (int64_t)(sp0 + u) * plane);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (sp0 + u < splits) s += v[u];
         }
         half4 o;
 #pragma unroll

@@ -1,6 +1,6 @@
 """Autotuner: fills csrc/dispatch_table.inc with the fastest specialisation per (M,N,K).
 
-    python -m paper_2512_02551_amd.tune [--workloads C1,C2,C3,C4,C5] [--out-log FILE] [--resume]
+    python -m paper_2512_02551_amd.tune [--workloads C1,C2,C3,C4,C5,P] [--out-log FILE] [--resume]
 
 Protocol (after the library-autotuning procedure the paper describes in Section 2.2.3 and
 its appendix: enumerate candidates, time each with warm-up rounds and a shuffled order per
@@ -46,6 +46,9 @@ def all_shapes(workloads):
         out += wl.c4_shapes()
     if "C5" in workloads:
         out += list(wl.C5_SHAPES) + [wl.C5_INT_SHAPE]
+    if "P" in workloads:       # the paper's full grid: all 10^3 triples over {64, ..., 16384} (Abstract)
+        v = wl.PAPER_GRID_VALUES
+        out += [(m, n, k) for m in v for n in v for k in v]
     seen, uniq = set(), []
     for s in out:
         if s not in seen:
@@ -182,11 +185,12 @@ def main():
             continue
         # coarse pass, shuffled order per round group
         for entry in plans:
-            timed(entry[1], a, b, c, 2)
+            timed(entry[1], a, b, c, 2 if 2.0 * M * N * K < 2e12 else 1)
         order = list(range(len(plans)))
         rng.shuffle(order)
+        coarse = args.coarse if 2.0 * M * N * K < 2e12 else max(2, args.coarse // 3)
         for i in order:
-            plans[i][2] += timed(plans[i][1], a, b, c, args.coarse)
+            plans[i][2] += timed(plans[i][1], a, b, c, coarse)
         plans.sort(key=lambda e: float(np.median(e[2])))
         best = plans[:args.top]
         for entry in best:
