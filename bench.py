@@ -56,6 +56,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spec", default=None, help="force one specialisation for every shape (tuning aid)")
     ap.add_argument("--table", action="store_true", help="print the per-shape table to stderr")
+    ap.add_argument("--server", action="store_true",
+                    help="server mode (Section 2.4.2): calls separated by random idle gaps of 0-2 ms, each call "
+                         "bracketed by its own events; the gaps are not part of any reported time")
     ap.add_argument("--per-call-events", action="store_true",
                     help="bracket every call with its own event pair (adds the event/launch gap to every call)")
     ap.add_argument("--calibrate", action="store_true",
@@ -155,9 +158,17 @@ def main():
     # consecutively without pauses), so a per-call time is that pair's elapsed time / K and carries no
     # event or launch gap.  With --cold the K calls rotate through operand sets whose total exceeds the
     # last-level cache.  "--per-call-events" brackets every single call instead.
+    import random
+    gap_rng = random.Random(0)
+    if args.server:
+        args.per_call_events = True
+
     def run_shape(s, k0, count, events=None):
         for k in range(count):
             a, b, c = s["bufs"][(k0 + k) % len(s["bufs"])]
+            if args.server and events is not None:
+                torch.cuda.synchronize()                       # the device is idle during the gap
+                time.sleep(gap_rng.uniform(0.0, 2e-3))
             if events is not None:
                 events[k][0].record(stream)
             s["plan"].run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
@@ -242,7 +253,8 @@ def main():
                          "C4": "200-shape grid from {64..12288}^3, uniform[-1,1]",
                          "C5": "16384x16384x{8192,16384}, uniform[-1,1]"}[args.workload],
             "layout": "NN row-major", "cache": "cold" if args.cold else "warm",
-            "timing": "per-call events" if args.per_call_events else "K back-to-back calls per shape between one event pair",
+            "timing": ("server mode: random idle gaps, per-call events" if args.server else
+                       "per-call events" if args.per_call_events else "K back-to-back calls per shape between one event pair"),
             "aggregate_tflops": total_flop * args.steps / wall * 1e-12,
         },
         "roofline": roofline,

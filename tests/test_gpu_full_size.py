@@ -93,3 +93,25 @@ def test_c5_large_16384_k8192_sampled():
     c, _, _, desc = run_hgemm(a, b)
     worst = _check_sampled(a, b, c, 3000, f"C5 {shape} {desc}")
     print(f"C5 {shape} [{desc}] worst error {worst:.3g} of the bound")
+
+
+@pytest.mark.parametrize("shape", [(520, 1032, 776), (72, 4104, 1016), (3000, 5000, 136), (24, 8200, 2056), (1, 1000, 12296),
+                                   (4100, 264, 4104), (8, 8, 16392), (2056, 2056, 2056), (6000, 6008, 520)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_shapes_outside_the_table_use_the_rules(shape):
+    """Shapes the dispatch table does not hold (ragged tiles in every dimension): planned by the
+    rules, checked on sampled positions with real inputs and bit for bit with exact integers."""
+    M, N, K = shape
+    rng = np.random.default_rng([M, N, K])
+    a = wl.uniform_pm1(rng, M, K)
+    b = wl.uniform_pm1(rng, K, N)
+    c, before, after, desc = run_hgemm(a, b, guard=1)
+    assert desc.startswith("mfma"), desc
+    _check_sampled(a, b, c, 2500, f"{shape} {desc}")
+    assert np.isnan(before).all() and np.isnan(after).all()
+    name, ai, bi = wl.exact_family_for(shape, seed=3)
+    ci, _, _, _ = run_hgemm(ai, bi)
+    ii, jj = wl.sample_positions(shape, 2500, seed=2)
+    ref = orc.hgemm_at(ai, bi, ii, jj)
+    sel = np.abs(ref.astype(np.float64)) <= 2048
+    assert np.array_equal(ci[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {name} {desc}"
