@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--cold", action="store_true", help="rotate operand sets so caches are cold")
+    ap.add_argument("--layout", default="nn", choices=["nn", "tn"],
+                    help="nn: B row-major (K x N); tn: B column-major, stored N x K (Section 2.2.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spec", default=None, help="force one specialisation for every shape (tuning aid)")
     ap.add_argument("--table", action="store_true", help="print the per-shape table to stderr")
@@ -141,11 +143,13 @@ def main():
             per_set = 2 * (M * K + K * N + M * N)
             n_sets = max(2, min(64, math.ceil(768 * 2 ** 20 / per_set)))
         group = []
+        if args.layout == "tn":
+            b = np.ascontiguousarray(b.T)
         da, db = upload(a), upload(b)
         for i in range(n_sets):
             group.append((da if i == 0 else da.clone(), db if i == 0 else db.clone(),
                           torch.empty((M, N), dtype=torch.float16, device="cuda")))
-        plan = hg.Plan(M, N, K, None, args.spec)
+        plan = hg.Plan(M, N, K, hg.Layouts.make(b_col_major=(args.layout == "tn")), args.spec)
         sets.append({"shape": (M, N, K), "bufs": group, "plan": plan, "desc": plan.describe(),
                      "info": plan.launch_info()})
     torch.cuda.synchronize()
@@ -252,7 +256,7 @@ def main():
                          "C3": "LLM-projection skinny shapes, A~N(0,1), B~N(0,0.02^2)",
                          "C4": "200-shape grid from {64..12288}^3, uniform[-1,1]",
                          "C5": "16384x16384x{8192,16384}, uniform[-1,1]"}[args.workload],
-            "layout": "NN row-major", "cache": "cold" if args.cold else "warm",
+            "layout": "NN row-major" if args.layout == "nn" else "TN (B column-major)", "cache": "cold" if args.cold else "warm",
             "timing": ("server mode: random idle gaps, per-call events" if args.server else
                        "per-call events" if args.per_call_events else "K back-to-back calls per shape between one event pair"),
             "aggregate_tflops": total_flop * args.steps / wall * 1e-12,

@@ -181,6 +181,32 @@ bool table_lookup(int64_t M, int64_t N, int64_t K, Spec* out)
     return false;
 }
 
+// A shape the table does not hold borrows the specialisation of the nearest tuned shape (distance
+// = sum of |log2| ratios of the three dimensions) when one lies within a factor of about two in
+// total; beyond that the rules above decide.
+bool nearest_neighbour(int64_t M, int64_t N, int64_t K, Spec* out)
+{
+    double best = 1e30;
+    const DispatchRow* arg = nullptr;
+    for (size_t i = 0; i < sizeof(kDispatchTable) / sizeof(kDispatchTable[0]); ++i) {
+        const DispatchRow& r = kDispatchTable[i];
+        if (r.spec[0] == '\0' || r.m <= 0 || r.n <= 0 || r.k <= 0) continue;
+        const double d = std::fabs(std::log2((double)M / (double)r.m)) + std::fabs(std::log2((double)N / (double)r.n)) +
+                         std::fabs(std::log2((double)K / (double)r.k));
+        if (d < best) { best = d; arg = &r; }
+    }
+    if (!arg || best > 1.25) return false;
+    Spec s;
+    if (!parse_spec(arg->spec, &s) || s.fam != FAM_MFMA) return false;
+    // keep the work per split of the neighbour rather than its split count
+    if (s.sk > 1) {
+        const double per = (double)arg->k / s.sk;
+        s.sk = (int)std::max<int64_t>(1, std::min<int64_t>(64, (int64_t)std::llround((double)K / per)));
+    }
+    *out = s;
+    return true;
+}
+
 hgemm_status_t finish_plan(hgemm_plan_s* p)
 {
     const int64_t M = p->M, N = p->N, K = p->K;
@@ -308,7 +334,9 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
             st = finish_plan(p);
         } else {
             const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
-            if (!table_lookup(M, N, K, &p->spec) || !packed) p->spec = heuristic(M, N, K);
+            if (!table_lookup(M, N, K, &p->spec) || !packed) {
+                if (!nearest_neighbour(M, N, K, &p->spec)) p->spec = heuristic(M, N, K);
+            }
             if (l.b == HGEMM_COL_MAJOR) p->spec.tb = 0;      // B already has K contiguous
             st = finish_plan(p);
             if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
