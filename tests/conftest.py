@@ -1,4 +1,4 @@
-"""pytest configuration: marker registration and import path."""
+"""pytest configuration: marker registration, import path, and a built library for the host-side tests."""
 import os
 import sys
 
@@ -9,3 +9,12 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+
+
+def pytest_sessionstart(session):
+    # A fresh checkout has no libhgemm.so (built artefacts are not committed).  The host-side tests
+    # load it, so compile it once if it is missing; an existing library is used as it is.
+    from paper_2512_02551_amd import build
+
+    if not os.path.exists(build.LIB):
+        build.build(force=True)
