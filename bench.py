@@ -42,7 +42,7 @@ MEASURED_TRAFFIC_BYTES = {
     (1024, 1024, 1024): (2.0 * 6185.5 + 2048.0) * 1024,
     (2048, 2048, 2048): (2.0 * 24648.4 + 8192.0) * 1024,
     (4096, 4096, 4096): (2.0 * 98382.1 + 32768.0) * 1024,
-    (8192, 8192, 8192): (2.0 * 789658.9 + 131072.0) * 1024,
+    (8192, 8192, 8192): (2.0 * 806885.9 + 131072.0) * 1024,
 }
 
 

@@ -259,6 +259,29 @@ def test_overflow_rounds_to_infinity():
     assert np.isinf(ref).all() and np.array_equal(c.view(np.uint16), ref.view(np.uint16))
 
 
+@pytest.mark.parametrize("spec", [None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=2,gm=8", "generic"])
+def test_subnormal_inputs_and_outputs_are_not_flushed(spec):
+    """fp16 subnormals are ordinary values of the format (Section 2.1 puts no range limit on A, B, C):
+    A holds multiples of 2^-24 below the smallest normal, B small integers, so every C element is an
+    exactly representable subnormal (|C| <= 3*2*96 units of 2^-24) and must match bit for bit.  A second
+    case reaches subnormal results from normal inputs (2^-14 * 2^-10)."""
+    M, N, K = 72, 136, 96
+    rng = np.random.default_rng(77)
+    a = (rng.integers(-3, 4, size=(M, K)).astype(np.float64) * 2.0 ** -24).astype(np.float16)
+    b = wl.integers(rng, K, N, -2, 2)
+    ref = orc.hgemm(a, b)
+    assert (np.abs(ref.astype(np.float64)) < 2.0 ** -14).all() and np.count_nonzero(ref) > M * N // 2
+    c, _, _, desc = run_hgemm(a, b, spec=spec)
+    assert_bit_exact(c, ref, "subnormal A: " + desc)
+    a2 = np.full((M, K), 2.0 ** -14, dtype=np.float16)
+    b2 = np.zeros((K, N), dtype=np.float16)
+    b2[np.arange(K), np.arange(K)] = 2.0 ** -10          # C[:, j] = 2^-24 for j < K, else 0
+    ref2 = orc.hgemm(a2, b2)
+    assert ref2[0, 0] == np.float16(2.0 ** -24) and ref2[0, N - 1] == 0
+    c2, _, _, desc = run_hgemm(a2, b2, spec=spec)
+    assert_bit_exact(c2, ref2, "subnormal C: " + desc)
+
+
 def test_leading_dimensions():
     M, N, K = 96, 80, 72
     lda, ldb, ldc = 88, 96, 104
