@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the roofline calibration kernels (MFMA-only loop, 1 GiB streaming read, "
                          "128 MiB fill) -- kernels of known size for scaling profiler counters")
+    ap.add_argument("--library-context", action="store_true",
+                    help="also time torch.matmul (the vendor GEMM library the PyTorch build ships) on the same "
+                         "operands with the same protocol; context only, the library under test never calls it")
     return ap.parse_args()
 
 
@@ -264,6 +267,39 @@ def main():
         "roofline": roofline,
         "per_shape": per_shape,
     }
+    if args.library_context:
+        # Context, as the paper quotes its kernels beside the vendor library (Section 2.2): same operands,
+        # same back-to-back protocol, output into a preallocated tensor.
+        lib_rows = []
+        for s in sets:
+            M, N, K = s["shape"]
+            outs = [torch.empty_like(c) for (_, _, c) in s["bufs"]]
+
+            def lib_calls(k0, count):
+                for k in range(count):
+                    a, b, _ = s["bufs"][(k0 + k) % len(s["bufs"])]
+                    torch.matmul(a, b.t() if args.layout == "tn" else b, out=outs[(k0 + k) % len(outs)])
+
+            lib_calls(0, args.warmup)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            lib_calls(args.warmup, args.steps)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            lib_rows.append({"shape": [M, N, K], "mean_us": ms * 1e3, "tflops": 2.0 * M * N * K / ms * 1e-9,
+                             "gbs": 2.0 * (M * K + K * N + M * N) / ms * 1e-6})
+            del outs
+        out["library_context"] = {
+            "what": "torch.matmul of this PyTorch build on the same operands and protocol (context only)",
+            "geomean_tflops": math.exp(sum(math.log(r["tflops"]) for r in lib_rows) / len(lib_rows)),
+            "per_shape": lib_rows,
+        }
+        if args.table:
+            for r, p in zip(lib_rows, per_shape):
+                print("{:>18s}  torch.matmul {:9.1f} us {:8.1f} TFLOP/s {:8.1f} GB/s   torch.matmul time / this library's time = {:.2f}".format(
+                    "x".join(map(str, r["shape"])), r["mean_us"], r["tflops"], r["gbs"], r["mean_us"] / p["mean_us"]), file=sys.stderr)
     if args.calibrate:
         ms, flop = hg.calibrate_mfma(20000, sh)
         buf = torch.ones(1 << 28, dtype=torch.int32, device="cuda")           # 1 GiB
