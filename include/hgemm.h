@@ -12,7 +12,7 @@
  *
  * One plan per (M,N,K,layout): the paper's premise (Abstract, Section 5) is
  * that every shape wants its own kernel configuration; hgemm_plan() looks the
- * shape up in a table of measured choices and falls back to rules.
+ * shape up in a table of measured choices and falls back to a fitted cost model.
  *
  * Threading: functions are thread-compatible (no global mutable state apart
  * from a read-only table); a single plan must not be run on two streams at
@@ -125,6 +125,13 @@ const char* hgemm_spec_help(void);
  * fit.                                                                      */
 hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K,
                                 const hgemm_layouts_t* layouts, char* buf, size_t n);
+
+/* The planner's cost model: predicted microseconds of one call of `spec` (an "mfma" spec without
+ * tb/sm) on an M x N x K problem.  hgemm_plan() picks the compiled configuration and split factor
+ * with the smallest prediction when its measured table has no row for the shape (Section 6 reads
+ * such trends -- tile size against M and N, stages against K -- off the paper's winners; here they
+ * are a fitted model of one launch).  Host only.  Errors: INVALID_ARG, UNSUPPORTED.            */
+hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spec, double* us);
 
 /* Tile-count arithmetic of the zero-padding technique (Section 5.2): number
  * of tiles along a dimension of size `dim` with tile size `tile`, and the

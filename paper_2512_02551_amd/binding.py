@@ -17,7 +17,7 @@ EXPORTS = (
     "hgemm_plan", "hgemm_plan_override", "hgemm_run", "hgemm_destroy", "hgemm_status_string",
     "hgemm_plan_describe", "hgemm_plan_workspace_bytes", "hgemm_plan_launch_info", "hgemm_spec_help",
     "hgemm_candidates", "hgemm_tiles", "hgemm_padded", "hgemm_tile_of_workgroup",
-    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read",
+    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us",
 )
 
 ROW_MAJOR, COL_MAJOR = 0, 1
@@ -84,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.hgemm_spec_help.argtypes = []
     lib.hgemm_candidates.restype = ci
     lib.hgemm_candidates.argtypes = [i64, i64, i64, lp, ctypes.c_char_p, ctypes.c_size_t]
+    lib.hgemm_predict_us.restype = ci
+    lib.hgemm_predict_us.argtypes = [i64, i64, i64, cp, ctypes.POINTER(ctypes.c_double)]
     lib.hgemm_tiles.restype = i64
     lib.hgemm_tiles.argtypes = [i64, i64]
     lib.hgemm_padded.restype = i64
@@ -135,6 +137,15 @@ def candidates(M: int, N: int, K: int, layouts: Optional[Layouts] = None) -> lis
     if st != 0:
         raise HgemmError(st, "hgemm_candidates")
     return [s for s in buf.value.decode().split("\n") if s]
+
+
+def predict_us(M: int, N: int, K: int, spec: str) -> float:
+    """The planner's cost-model prediction for one specialisation (host only)."""
+    us = ctypes.c_double()
+    st = load().hgemm_predict_us(M, N, K, spec.encode(), ctypes.byref(us))
+    if st != 0:
+        raise HgemmError(st, f"hgemm_predict_us({spec!r})")
+    return us.value
 
 
 class Plan:

@@ -181,30 +181,128 @@ bool table_lookup(int64_t M, int64_t N, int64_t K, Spec* out)
     return false;
 }
 
-// A shape the table does not hold borrows the specialisation of the nearest tuned shape (distance
-// = sum of |log2| ratios of the three dimensions) when one lies within a factor of about two in
-// total; beyond that the rules above decide.
-bool nearest_neighbour(int64_t M, int64_t N, int64_t K, Spec* out)
+// ---------------------------------------------------------------------------
+// Plan-time cost model for shapes the table does not hold.  Section 6 of the paper reads trends off
+// its per-shape winners; here the dependence on (M, N, K) is an explicit model of one launch --
+// matrix-core and copy time per K-tile, prologue/epilogue per workgroup, rounds over the compute
+// units, whole-problem memory time, the second pass of split-K -- with constants fitted to measured
+// times of all candidates on random shapes (plan_model.py holds the same formula and the fit).
+// ---------------------------------------------------------------------------
+struct PlanModel {
+#define PLAN_MODEL_CONST(name, value) double name = value;
+#include "plan_model.inc"
+#undef PLAN_MODEL_CONST
+};
+const PlanModel kModel;
+
+constexpr int64_t kCUs = 256;
+constexpr int64_t kLdsPerCU = 160 * 1024;
+constexpr double kCacheResidentBytes = 192.0 * 1024 * 1024;
+
+// Split count finish_plan() will actually use: ranges are whole K-tiles, empty splits are dropped.
+int64_t effective_splits(int64_t ktiles, int64_t sk)
 {
-    double best = 1e30;
-    const DispatchRow* arg = nullptr;
-    for (size_t i = 0; i < sizeof(kDispatchTable) / sizeof(kDispatchTable[0]); ++i) {
-        const DispatchRow& r = kDispatchTable[i];
-        if (r.spec[0] == '\0' || r.m <= 0 || r.n <= 0 || r.k <= 0) continue;
-        const double d = std::fabs(std::log2((double)M / (double)r.m)) + std::fabs(std::log2((double)N / (double)r.n)) +
-                         std::fabs(std::log2((double)K / (double)r.k));
-        if (d < best) { best = d; arg = &r; }
+    sk = std::min<int64_t>(sk, std::max<int64_t>(ktiles, 1));
+    if (sk < 1) sk = 1;
+    const int64_t per = (ktiles + sk - 1) / sk;
+    return std::max<int64_t>(1, (ktiles + per - 1) / std::max<int64_t>(per, 1));
+}
+
+// Split factors worth considering for a configuration with `t` tiles and `ktiles` K-tiles.
+std::vector<int> split_candidates(int64_t t, int64_t ktiles)
+{
+    std::vector<int> sks = {1};
+    if (t < 2 * kCUs) {
+        for (int sk : {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64}) {
+            if (ktiles / sk < 2) break;
+            if (t * sk > 8 * kCUs) break;
+            sks.push_back(sk);
+        }
     }
-    if (!arg || best > 1.25) return false;
-    Spec s;
-    if (!parse_spec(arg->spec, &s) || s.fam != FAM_MFMA) return false;
-    // keep the work per split of the neighbour rather than its split count
-    if (s.sk > 1) {
-        const double per = (double)arg->k / s.sk;
-        s.sk = (int)std::max<int64_t>(1, std::min<int64_t>(64, (int64_t)std::llround((double)K / per)));
-    }
-    *out = s;
+    return sks;
+}
+
+// Tiles far taller or wider than the problem only waste matrix-core work.
+bool tile_fits_problem(const MfmaEntry& e, int64_t M, int64_t N)
+{
+    if (e.bm >= 2 * M && e.bm > 32) return false;
+    if (e.bn >= 2 * N && e.bn > 64) return false;
     return true;
+}
+
+// Predicted microseconds of one call (plain or split-K kernel, default tile order).
+double predict_us(int64_t Mi, int64_t Ni, int64_t Ki, int bm, int bn, int bk, int wm, int wn, int st, int pf, int64_t ski)
+{
+    const PlanModel& g = kModel;
+    const double M = (double)Mi, N = (double)Ni, K = (double)Ki;
+    const int nw = wm * wn;
+    const double tiles = (double)(((Mi + bm - 1) / bm) * ((Ni + bn - 1) / bn));
+    const double kt = (double)((Ki + bk - 1) / bk);
+    const double sk = (double)ski;
+    const int64_t lds = (int64_t)st * (bm + bn) * bk * 2;
+    const int tm = bm / wm / 32, tn = bn / wn / 32;
+    const int regs = tm * tn * 16 + (pf + 1) * (tm + tn) * 4 + 40;       // accumulators + fragment sets + addressing
+    const int wps = std::max(1, std::min(8, 512 / std::max(regs, 64)));  // waves per SIMD the register file admits
+    const double occ = (double)std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds, nw <= wps * 4 ? (wps * 4) / nw : 1));
+
+    const double wgs = tiles * sk;
+    const double kt_wg = std::ceil(kt / sk);
+    const double w = std::ceil(wgs / (double)kCUs);
+    const double co = std::min(occ, w);
+    const double rounds = std::ceil(w / co);
+    const double flop = 2.0 * M * N * K;
+    const double big = std::min(2.0, std::max(0.0, std::log10(std::max(flop, 1.0)) - 10.0)) / 2.0;
+    double t_mfma = 2.0 * bm * bn * bk / g.F * (1.0 + g.c1 * (double)(tm + tn) / (double)(tm * tn)) * (1.0 + g.cp * big);
+    if (pf == 1) t_mfma *= g.q1;
+    if (bm == 32) t_mfma *= g.m32;
+    if (bk == 128) t_mfma *= g.k128; else if (bk == 32) t_mfma *= g.k32;
+    const double stage = (double)(bm + bn) * bk * 2.0;
+    const double bytes_in = 2.0 * (M * K + K * N);
+    const double bytes_c = 2.0 * M * N;
+    const double part = ski > 1 ? sk * M * N * 4.0 : 0.0;
+    const bool resident = bytes_in + bytes_c < kCacheResidentBytes;
+    const double miss = std::min(1.0, bytes_in / (wgs * kt_wg * stage));
+    const double lat = g.L + miss * (resident ? 0.0 : g.Lh);
+    double peak = g.BW * (nw == 2 ? g.a2 : nw == 8 ? g.a8 : nw == 16 ? g.a16 : 1.0);
+    peak *= (bn == 64 ? g.b64 : bn == 256 ? g.b256 : 1.0);
+    const double inflight = (double)std::max(st - 1, 1) * stage * co;
+    const double bw = std::min(peak, inflight / lat) / co;
+    const double t_copy = stage / bw;
+    const double t_kt = std::max(t_mfma * co, t_copy) + g.ov * std::min(t_mfma * co, t_copy) + g.tk;        // ns
+    const double pro = g.Tpro;
+    const double epi = g.e0 + (ski > 1 ? bm * bn * 4.0 / g.BWp : bm * bn * 2.0 / g.BWepi) * 1e-3;
+    const double cu_time = rounds * (kt_wg * t_kt * 1e-3 + pro + epi);
+    const double tot_inflight = std::min(wgs, (double)kCUs * occ) * (double)std::max(st - 1, 1) * stage;
+    const double bw_read = (resident && part + bytes_in + bytes_c < kCacheResidentBytes) ? g.BWs : std::min(g.BWh, tot_inflight / g.Lhb);
+    const double writes = ski > 1 ? part : bytes_c;
+    const double t_main = std::max(cu_time, bytes_in / bw_read * 1e-3) + writes / (co <= 1.0 ? g.BWw1 : g.BWw2) * 1e-3;
+    const double t_red = ski > 1 ? g.Tr0 + g.Tr1 * std::ceil(sk / 8.0) + (part + bytes_c) / g.BWr * 1e-3 : 0.0;
+    return g.T0 + t_main + t_red;
+}
+
+// The cheapest compiled configuration and split factor under the model.
+bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out)
+{
+    double best = 1e300;
+    bool found = false;
+    for (const MfmaEntry& e : registry()) {
+        if (!tile_fits_problem(e, M, N)) continue;
+        const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
+        const int64_t ktiles = (K + e.bk - 1) / e.bk;
+        for (int sk0 : split_candidates(t, ktiles)) {
+            const int64_t sk = effective_splits(ktiles, sk0);
+            const double us = predict_us(M, N, K, e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf, sk);
+            if (us < best) {
+                best = us;
+                found = true;
+                Spec s;
+                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf;
+                s.sk = (int)sk; s.gm = 8;
+                *out = s;
+            }
+        }
+    }
+    return found;
 }
 
 hgemm_status_t finish_plan(hgemm_plan_s* p)
@@ -243,10 +341,8 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     a.swizzle = s.gm;
     // split K into ranges that are multiples of BK; drop splits that would be empty
     int64_t ktiles = (K + e->bk - 1) / e->bk;
-    int64_t sk = std::min<int64_t>(s.sk, std::max<int64_t>(ktiles, 1));
-    int64_t per = (ktiles + sk - 1) / sk;
-    sk = (ktiles + per - 1) / std::max<int64_t>(per, 1);
-    if (sk < 1) sk = 1;
+    const int64_t sk = effective_splits(ktiles, s.sk);
+    const int64_t per = (ktiles + sk - 1) / sk;
     if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
     s.sk = (int)sk;
     a.splits = (int)sk;
@@ -335,7 +431,7 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
         } else {
             const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
             if (!table_lookup(M, N, K, &p->spec) || !packed) {
-                if (!nearest_neighbour(M, N, K, &p->spec)) p->spec = heuristic(M, N, K);
+                if (!model_choice(M, N, K, &p->spec)) p->spec = heuristic(M, N, K);
             }
             if (l.b == HGEMM_COL_MAJOR) p->spec.tb = 0;      // B already has K contiguous
             st = finish_plan(p);
@@ -528,19 +624,10 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
     } else {
         const int64_t CUS = 256;
         for (const MfmaEntry& e : registry()) {
-            // tiles far taller/wider than the problem only waste matrix-core work
-            if (e.bm >= 2 * M && e.bm > 32) continue;
-            if (e.bn >= 2 * N && e.bn > 64) continue;
+            if (!tile_fits_problem(e, M, N)) continue;
             const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
             const int64_t ktiles = (K + e.bk - 1) / e.bk;
-            std::vector<int> sks = {1};
-            if (t < 2 * CUS) {
-                for (int sk : {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64}) {
-                    if (ktiles / sk < 2) break;
-                    if (t * sk > 8 * CUS) break;
-                    sks.push_back(sk);
-                }
-            }
+            const std::vector<int> sks = split_candidates(t, ktiles);
             if (t % CUS != 0 && ktiles >= 4 && e.bm >= 64 && e.bn >= 64) {
                 Spec s;
                 s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = 1; s.gm = 8; s.sm = 1;
@@ -567,6 +654,16 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
     }
     if (out.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
     memcpy(buf, out.c_str(), out.size() + 1);
+    return HGEMM_OK;
+}
+
+hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spec, double* us)
+{
+    if (!spec || !us || M <= 0 || N <= 0 || K <= 0) return HGEMM_ERR_INVALID_ARG;
+    Spec s;
+    if (!parse_spec(spec, &s)) return HGEMM_ERR_INVALID_ARG;
+    if (s.fam != FAM_MFMA || s.sm || s.tb || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
+    *us = predict_us(M, N, K, s.bm, s.bn, s.bk, s.wm, s.wn, s.st, s.pf, effective_splits((K + s.bk - 1) / s.bk, s.sk));
     return HGEMM_OK;
 }
 

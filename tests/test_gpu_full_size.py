@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, with the plans bench.py times (dispatch table / rules):
+"""GPU parity at the benchmark's full sizes, with the plans bench.py times (dispatch table / cost model):
 sampled outputs evaluated one by one by the oracle, and full comparison where the oracle finishes in seconds."""
 import numpy as np
 import pytest
@@ -98,10 +98,14 @@ def test_c5_large_16384_k8192_sampled():
 @pytest.mark.parametrize("shape", [(520, 1032, 776), (72, 4104, 1016), (3000, 5000, 136), (24, 8200, 2056), (1, 1000, 12296),
                                    (4100, 264, 4104), (8, 8, 16392), (2056, 2056, 2056), (6000, 6008, 520)],
                          ids=lambda s: "x".join(map(str, s)))
-def test_shapes_outside_the_table_use_the_rules(shape):
+def test_shapes_outside_the_table_use_the_cost_model(shape):
     """Shapes the dispatch table does not hold (ragged tiles in every dimension): planned by the
-    rules, checked on sampled positions with real inputs and bit for bit with exact integers."""
+    cost model, checked on sampled positions with real inputs and bit for bit with exact integers."""
     M, N, K = shape
+    with hg.Plan(M, N, K) as p:
+        chosen = p.describe()
+    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and "gm=8" in s]
+    assert hg.predict_us(M, N, K, chosen) <= min(hg.predict_us(M, N, K, s) for s in cands) * (1 + 1e-12), chosen
     rng = np.random.default_rng([M, N, K])
     a = wl.uniform_pm1(rng, M, K)
     b = wl.uniform_pm1(rng, K, N)
