@@ -1,5 +1,5 @@
 // Host side of the C ABI declared in include/hgemm.h: plan construction (spec
-// parsing, dispatch table lookup, heuristics), launch, and helpers.
+// parsing, dispatch table lookup, plan-time cost model), launch, and helpers.
 #include "../../include/hgemm.h"
 
 #include <hip/hip_runtime.h>
@@ -137,7 +137,8 @@ bool fast_path_ok(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l)
     return true;
 }
 
-// Rules used when the measured table has no row for the shape.  They follow the trends of
+// Last-resort rules, used only when neither the table nor the cost model yields a kernel this
+// build holds.  They follow the trends of
 // Section 6 (tile height/width grow with M/N; more stages for long K) with MI355X numbers:
 // 256 CUs want >= 256 workgroups, so small problems take smaller tiles or split K.
 Spec heuristic(int64_t M, int64_t N, int64_t K)

@@ -68,7 +68,7 @@ def write_table(log_path: str, table_path: str = TABLE) -> int:
                     rows[tuple(r["shape"])] = r
     with open(table_path, "w") as f:
         f.write("// Per-shape dispatch table: (M, N, K) -> specialisation, filled from timed runs on one MI355X\n"
-                "// by the autotuner (python -m paper_2512_02551_amd.tune).  An empty spec means \"use the rules\".\n"
+                "// by the autotuner (python -m paper_2512_02551_amd.tune).  An empty spec means \"use the cost model\".\n"
                 "// Columns of the trailing comment: median microseconds, TFLOP/s, GB/s of algorithmic traffic.\n"
                 "struct DispatchRow { int64_t m, n, k; const char* spec; };\n"
                 "static const DispatchRow kDispatchTable[] = {\n"
