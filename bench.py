@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the roofline calibration kernels (MFMA-only loop, 1 GiB streaming read, "
                          "128 MiB fill) -- kernels of known size for scaling profiler counters")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each shape's K back-to-back calls in a HIP graph and time its replay: removes the "
+                         "host's enqueue rate (about 3.4 us per call from Python) from launch-bound small shapes")
     ap.add_argument("--library-context", action="store_true",
                     help="also time torch.matmul (the vendor GEMM library the PyTorch build ships) on the same "
                          "operands with the same protocol; context only, the library under test never calls it")
@@ -170,7 +173,7 @@ def main():
     if args.server:
         args.per_call_events = True
 
-    def run_shape(s, k0, count, events=None):
+    def run_shape(s, k0, count, events=None, sh=sh):
         for k in range(count):
             a, b, c = s["bufs"][(k0 + k) % len(s["bufs"])]
             if args.server and events is not None:
@@ -189,11 +192,26 @@ def main():
     pair = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sets]
     per_call = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
                 for _ in sets] if args.per_call_events else None
+    graphs = None
+    if args.graph:
+        if per_call:
+            print("bench.py: --graph times whole replays; it cannot be combined with per-call events", file=sys.stderr)
+            sys.exit(2)
+        graphs = []
+        for s in sets:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run_shape(s, args.warmup, args.steps, None, torch.cuda.current_stream().cuda_stream)
+            g.replay()                              # one untimed replay
+            graphs.append(g)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for si, s in enumerate(sets):
         pair[si][0].record(stream)
-        run_shape(s, args.warmup, args.steps, per_call[si] if per_call else None)
+        if graphs:
+            graphs[si].replay()
+        else:
+            run_shape(s, args.warmup, args.steps, per_call[si] if per_call else None)
         pair[si][1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -261,7 +279,9 @@ def main():
                          "C5": "16384x16384x{8192,16384}, uniform[-1,1]"}[args.workload],
             "layout": "NN row-major" if args.layout == "nn" else "TN (B column-major)", "cache": "cold" if args.cold else "warm",
             "timing": ("server mode: random idle gaps, per-call events" if args.server else
-                       "per-call events" if args.per_call_events else "K back-to-back calls per shape between one event pair"),
+                       "per-call events" if args.per_call_events else
+                       "replay of a HIP graph holding K back-to-back calls per shape" if args.graph else
+                       "K back-to-back calls per shape between one event pair"),
             "aggregate_tflops": total_flop * args.steps / wall * 1e-12,
         },
         "roofline": roofline,

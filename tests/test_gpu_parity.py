@@ -323,3 +323,37 @@ def test_error_paths():
     assert e.value.status == 2
     with hg.Plan(64, 64, 64) as p:
         assert p.run_status(None, None, None) == 1                             # null pointers with work to do
+
+
+def test_runs_can_be_captured_in_a_graph_and_replayed():
+    """hgemm_run only launches kernels on the stream it is given, so a caller may capture it into a
+    graph (launch-bound loops of small GEMMs).  Plain, split-K, stream-K and transposing-copy plans are
+    captured together, the graph is replayed several times with eager work in between, and every replay
+    must reproduce the eager results bit for bit."""
+    shape = (300, 520, 1000)
+    name, a, b = wl.exact_family_for(shape, seed=9)
+    ref = orc.hgemm(a, b)
+    specs = [None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=3,gm=8", "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=1,gm=8,sm=1",
+             "mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=2,pf=1,sk=1,gm=8,tb=1"]
+    da, db = to_dev(a), to_dev(b)
+    plans = [hg.Plan(*shape, None, s) for s in specs]
+    outs = [torch.full((shape[0], shape[1]), float("nan"), dtype=torch.float16, device="cuda") for _ in plans]
+    try:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream().cuda_stream
+            for p, o in zip(plans, outs):
+                p.run(da.data_ptr(), db.data_ptr(), o.data_ptr(), cs)
+        for rep in range(3):
+            for o in outs:
+                o.fill_(float("nan"))
+            # unrelated eager work between replays
+            c_eager, _, _, _ = run_hgemm(a, b)
+            assert_bit_exact(c_eager, ref, "eager between replays")
+            g.replay()
+            torch.cuda.synchronize()
+            for p, o in zip(plans, outs):
+                assert_bit_exact(to_host(o), ref, f"replay {rep} {p.describe()}")
+    finally:
+        for p in plans:
+            p.destroy()
