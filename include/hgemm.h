@@ -60,7 +60,8 @@ typedef struct {
  *   M,N,K    >= 0.  M, N or K equal to 0 is valid (K = 0 gives C = 0).
  *   layouts  host pointer; NULL means NN, packed
  * Allocates the plan's device workspace (split-K partial sums, stream-K
- * fix-up buffers and flags) on the CURRENT device, if the choice needs one.
+ * partial tiles, padded copies of unaligned operands) on the CURRENT device,
+ * if the choice needs one.
  * Errors: INVALID_ARG, UNSUPPORTED, ALLOC, ARCH.
  */
 hgemm_status_t hgemm_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K,
@@ -72,7 +73,8 @@ hgemm_status_t hgemm_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K,
  * that must cover every kernel.  `spec` is a host string of the form
  *   "<family>[,key=value]..."    e.g.  "mfma,bm=256,bn=256,bk=64,st=2,sk=1"
  * Families and keys are listed by hgemm_spec_help().  A spec that cannot run
- * the shape (alignment, tile larger than the limits) returns UNSUPPORTED.
+ * the shape as it lies in memory (alignment, tile larger than the limits)
+ * returns UNSUPPORTED: an explicit spec never pads.
  */
 hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K,
                                    const hgemm_layouts_t* layouts, const char* spec);
@@ -81,10 +83,17 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
  * hgemm_run -- enqueue C = A*B on `hip_stream` (Section 2.1; the call shape
  * kernel(a, b, out) of Section 2.4.1's timing listing).
  *   A, B, C     DEVICE pointers to fp16, owned by the caller, non-overlapping.
- *               Fast kernels need 16-byte aligned bases and K, N (and the
- *               leading dimensions) multiples of 8; anything else silently
- *               takes the generic kernel.  C is write-only: every element is
- *               overwritten (beta = 0), earlier contents never leak.
+ *               The matrix-core kernels need 16-byte aligned bases and K, N
+ *               (and the leading dimensions) multiples of 8.  When K, N or a
+ *               leading dimension is not, hgemm_plan() arranges zero-padded
+ *               packed copies of A, B and C in the plan's workspace (Section
+ *               5.2's zero padding; two copy kernels before and one after the
+ *               GEMM, on the same stream), except for problems below 2^20
+ *               multiply-adds, which take a generic one-thread-per-element
+ *               kernel, as do calls whose base pointers are not 16-byte
+ *               aligned.  C is write-only: every element is overwritten
+ *               (beta = 0), earlier contents never leak, and nothing outside
+ *               the M x N elements of C is written.
  *   hip_stream  a hipStream_t passed as void*; NULL = the default stream.
  * Asynchronous; allocates nothing; all kernels (main, split-K reduction,
  * stream-K fix-up, the optional transposing copy of B) go to hip_stream in

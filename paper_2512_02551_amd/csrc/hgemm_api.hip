@@ -91,6 +91,7 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "gm") sp.gm = (int)v;
         else if (key == "tb") sp.tb = (int)v;
         else if (key == "sm") sp.sm = (int)v;
+        else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
     if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || (sp.sm && sp.sk > 1)) return false;
@@ -120,6 +121,14 @@ struct hgemm_plan_s {
     size_t partial_offset;      // byte offset of the partial sums inside the workspace
     bool tn_kernel;             // the MFMA kernel reads B with K contiguous
     int device;
+    // Zero padding (Section 5.2) for problems whose N, K or leading dimensions are not multiples of 8:
+    // M, N, K, lay above then describe packed, zero-filled copies in the workspace whose N and K are
+    // rounded up to 8, and the fields below keep the caller's problem.
+    bool padded;
+    int64_t uM, uN, uK;
+    hgemm_layouts_t ulay;
+    size_t a_off, b_off, c_off; // byte offsets of the padded copies of A, B and C inside the workspace
+    size_t bt_off;              // byte offset of the transposed copy of B (spec.tb)
 };
 
 namespace {
@@ -196,6 +205,7 @@ struct PlanModel {
 };
 const PlanModel kModel;
 
+constexpr double kPadMinMacs = 1024.0 * 1024;     // below this many multiply-adds an unaligned problem stays on the generic kernel
 constexpr int64_t kCUs = 256;
 constexpr int64_t kLdsPerCU = 160 * 1024;
 constexpr double kCacheResidentBytes = 192.0 * 1024 * 1024;
@@ -370,12 +380,22 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
             a.sk_workers = (int)((total + ipw - 1) / ipw);
         }
     }
-    size_t bt_bytes = s.tb ? (((size_t)N * (size_t)K * 2 + 255) / 256) * 256 : 0;
+    auto up256 = [](size_t b) { return ((b + 255) / 256) * 256; };
+    size_t pad_bytes = 0;
+    p->a_off = p->b_off = p->c_off = 0;
+    if (p->padded) {
+        p->a_off = 0;
+        p->b_off = up256((size_t)M * (size_t)K * 2);
+        p->c_off = p->b_off + up256((size_t)K * (size_t)N * 2);
+        pad_bytes = p->c_off + up256((size_t)M * (size_t)N * 2);
+    }
+    size_t bt_bytes = s.tb ? up256((size_t)N * (size_t)K * 2) : 0;
     size_t partial_bytes = sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
     if (s.sm) partial_bytes = (size_t)2 * a.sk_workers * e->bm * e->bn * sizeof(float);
-    partial_bytes = ((partial_bytes + 255) / 256) * 256;
-    p->partial_offset = bt_bytes;
-    p->workspace_bytes = bt_bytes + partial_bytes;
+    partial_bytes = up256(partial_bytes);
+    p->bt_off = pad_bytes;
+    p->partial_offset = pad_bytes + bt_bytes;
+    p->workspace_bytes = pad_bytes + bt_bytes + partial_bytes;
     if (p->workspace_bytes) {
         if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
             (void)hipGetLastError();
@@ -383,7 +403,7 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
             p->workspace_bytes = 0;
             return HGEMM_ERR_ALLOC;
         }
-        if (partial_bytes) a.partial = (float*)((char*)p->workspace + bt_bytes);
+        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
     }
     return HGEMM_OK;
 }
@@ -419,6 +439,9 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
     hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s;
     if (!p) return HGEMM_ERR_ALLOC;
     p->M = M; p->N = N; p->K = K; p->lay = l; p->device = dev;
+    p->padded = false;
+    p->uM = M; p->uN = N; p->uK = K; p->ulay = l;
+    p->a_off = p->b_off = p->c_off = p->bt_off = 0;
 
     hgemm_status_t st;
     if (spec_text) {
@@ -426,6 +449,24 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
         st = finish_plan(p);
     } else {
         bool fast = fast_path_ok(M, N, K, l) && M > 0 && N > 0 && K > 0;
+        if (!fast && M > 0 && N > 0 && K > 0 && (double)M * (double)N * (double)K >= kPadMinMacs) {
+            // N, K or a leading dimension is not a multiple of 8.  Above a size where the one-thread-per-
+            // element kernel would take longer than four extra launches, run the matrix-core kernel on
+            // packed copies whose N and K are rounded up to 8 and zero-filled (the paper's zero padding,
+            // Section 5.2, applied to the dimensions the 16-byte copies need aligned).
+            const int64_t Kp = (K + 7) / 8 * 8, Np = (N + 7) / 8 * 8;
+            hgemm_layouts_t lp = l;
+            lp.lda = Kp;
+            lp.ldb = (l.b == HGEMM_ROW_MAJOR) ? Np : Kp;
+            lp.ldc = Np;
+            if (fast_path_ok(M, Np, Kp, lp)) {
+                p->padded = true;
+                p->N = N = Np;
+                p->K = K = Kp;
+                p->lay = l = lp;
+                fast = true;
+            }
+        }
         if (!fast) {
             p->spec = Spec();
             st = finish_plan(p);
@@ -434,7 +475,7 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
             if (!table_lookup(M, N, K, &p->spec) || !packed) {
                 if (!model_choice(M, N, K, &p->spec)) p->spec = heuristic(M, N, K);
             }
-            if (l.b == HGEMM_COL_MAJOR) p->spec.tb = 0;      // B already has K contiguous
+            if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already
             st = finish_plan(p);
             if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
                 p->spec = heuristic(M, N, K);
@@ -478,6 +519,39 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     }
     if (!A || !B) return HGEMM_ERR_INVALID_ARG;
 
+    void* const user_C = C;
+    if (plan->padded) {
+        // zero-filled packed copies of A and B; the kernels below then see an aligned problem
+        char* ws = (char*)plan->workspace;
+        const hgemm_layouts_t& ul = plan->ulay;
+        auto copy = [&](const void* src, int64_t src_ld, int64_t src_rows, int64_t src_cols, void* dst, int64_t dst_ld, int64_t dst_rows,
+                        int64_t dst_cols) {
+            const dim3 grid((unsigned)((dst_cols + 2047) / 2048),
+                            (unsigned)std::min<int64_t>((dst_rows + kCopyRowsPerBlock - 1) / kCopyRowsPerBlock, 32768));
+            hipLaunchKernelGGL(copy2d_kernel<true>, grid, dim3(256), 0, stream, (const _Float16*)src, src_ld, src_rows, src_cols,
+                               (_Float16*)dst, dst_ld, dst_rows, dst_cols);
+        };
+        copy(A, ul.lda, plan->uM, plan->uK, ws + plan->a_off, K, M, K);
+        if (ul.b == HGEMM_ROW_MAJOR) copy(B, ul.ldb, plan->uK, plan->uN, ws + plan->b_off, N, K, N);
+        else copy(B, ul.ldb, plan->uN, plan->uK, ws + plan->b_off, K, N, K);
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        A = ws + plan->a_off;
+        B = ws + plan->b_off;
+        C = ws + plan->c_off;
+    }
+    // the padded output goes back to the caller's C (its N columns, its leading dimension)
+    auto finish = [&]() -> hgemm_status_t {
+        if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        if (plan->padded) {
+            const dim3 grid((unsigned)((plan->uN + 2047) / 2048),
+                            (unsigned)std::min<int64_t>((plan->uM + kCopyRowsPerBlock - 1) / kCopyRowsPerBlock, 32768));
+            hipLaunchKernelGGL(copy2d_kernel<false>, grid, dim3(256), 0, stream, (const _Float16*)C, N, M, N, (_Float16*)user_C,
+                               plan->ulay.ldc, plan->uM, plan->uN);
+            if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+        }
+        return HGEMM_OK;
+    };
+
     const bool aligned = ((((uintptr_t)A) | ((uintptr_t)B) | ((uintptr_t)C)) & 15) == 0;
     if (plan->spec.fam == FAM_GENERIC || !aligned) {
         if (N > (int64_t)64 * 0x7fffffff || (M + 3) / 4 > 65535) {
@@ -494,7 +568,7 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
                                (const _Float16*)A, (const _Float16*)B, (_Float16*)C, M, N, K, plan->lay.lda, plan->lay.ldb,
                                plan->lay.ldc, plan->lay.b == HGEMM_COL_MAJOR ? 1 : 0);
         }
-        return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
+        return finish();
     }
 
     GemmArgs a = plan->args;
@@ -506,9 +580,9 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     if (plan->spec.tb) {
         // B (K x N, row-major) -> workspace (N x K, row-major), then the K-contiguous kernel
         hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, stream,
-                           (const _Float16*)B, (_Float16*)plan->workspace, (int)K, (int)N, (int)plan->lay.ldb);
+                           (const _Float16*)B, (_Float16*)((char*)plan->workspace + plan->bt_off), (int)K, (int)N, (int)plan->lay.ldb);
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
-        a.B = (const _Float16*)plan->workspace;
+        a.B = (const _Float16*)((char*)plan->workspace + plan->bt_off);
     }
     if (plan->spec.sm) {
         hipLaunchKernelGGL(plan->tn_kernel ? e->streamk_tn : e->streamk, dim3((unsigned)(a.dp_tiles + a.sk_workers)), dim3(e->threads),
@@ -528,7 +602,7 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     } else {
         hipLaunchKernelGGL(plan->tn_kernel ? e->plain_tn : e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     }
-    return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
+    return finish();
 }
 
 hgemm_status_t hgemm_destroy(hgemm_plan_t plan)
@@ -557,7 +631,7 @@ const char* hgemm_status_string(hgemm_status_t status)
 hgemm_status_t hgemm_plan_describe(hgemm_plan_t plan, char* buf, size_t n)
 {
     if (!plan || !buf || n == 0) return HGEMM_ERR_INVALID_ARG;
-    const std::string s = spec_to_string(plan->spec);
+    const std::string s = spec_to_string(plan->spec) + (plan->padded ? ",pad=1" : "");
     if (s.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
     memcpy(buf, s.c_str(), s.size() + 1);
     return HGEMM_OK;
@@ -599,6 +673,8 @@ const char* hgemm_spec_help(void)
             "    tb = 1: copy row-major B transposed into the workspace first and run the K-contiguous kernel,\n"
             "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
             "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
+            "    pad = 1 in a description: N, K or a leading dimension is not a multiple of 8 and the kernel runs on\n"
+            "            zero-padded packed copies held in the plan's workspace (decided by hgemm_plan from the shape)\n"
             "    compiled (bm,bn,bk,wm,wn,st,pf):";
         for (const MfmaEntry& e : registry()) {
             char b[64];

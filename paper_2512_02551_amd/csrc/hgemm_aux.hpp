@@ -1,5 +1,5 @@
-// Auxiliary kernels: the generic any-shape GEMM, the split-K reduction, a transposing copy, a fill
-// kernel, and the two roofline calibration kernels.
+// Auxiliary kernels: the generic any-shape GEMM, the split-K reduction, a transposing copy, a padding
+// copy, a fill kernel, and the two roofline calibration kernels.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -89,6 +89,53 @@ __global__ __launch_bounds__(256) void transpose_kernel(const _Float16* __restri
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = tile[kc + e][n];
         if (n0 + n < N && k0 + kc < K) *(half8*)(out + (size_t)(n0 + n) * K + k0 + kc) = v;
+    }
+}
+
+// dst (dst_rows x dst_cols, leading dimension dst_ld) = src where src has an element, zero elsewhere.
+// Pads A and B before, and copies C back after, a kernel run on zero-padded copies.  One side of every
+// such copy is a packed workspace matrix (base 256-byte aligned, columns and leading dimension multiples
+// of 8) and moves 16 bytes per lane; the caller's side may start its rows at odd element offsets and is
+// accessed two bytes at a time.  A thread handles 8 consecutive columns of kCopyRowsPerBlock rows.
+// WIDE_DST: the destination is the workspace side (padding); otherwise the source is (copy-back).
+constexpr int kCopyRowsPerBlock = 4;
+template <bool WIDE_DST>
+__global__ __launch_bounds__(256) void copy2d_kernel(const _Float16* __restrict__ src, int64_t src_ld, int64_t src_rows, int64_t src_cols,
+                                                     _Float16* __restrict__ dst, int64_t dst_ld, int64_t dst_rows, int64_t dst_cols)
+{
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c0 >= dst_cols) return;
+    for (int64_t rb = (int64_t)blockIdx.y * kCopyRowsPerBlock; rb < dst_rows; rb += (int64_t)gridDim.y * kCopyRowsPerBlock) {
+        half8 v[kCopyRowsPerBlock];
+        // all loads of the block's rows first, then the stores: the rows are independent
+#pragma unroll
+        for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+            const int64_t r = rb + j;
+            v[j] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (r < src_rows && r < dst_rows) {
+                if (!WIDE_DST && c0 + 8 <= src_cols) {
+                    v[j] = *(const half8*)(src + r * src_ld + c0);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (c0 + e < src_cols) v[j][e] = src[r * src_ld + c0 + e];
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+            const int64_t r = rb + j;
+            if (r < dst_rows) {
+                if (WIDE_DST && c0 + 8 <= dst_cols) {
+                    *(half8*)(dst + r * dst_ld + c0) = v[j];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (c0 + e < dst_cols) dst[r * dst_ld + c0 + e] = v[j][e];
+                }
+            }
+        }
     }
 }
 

@@ -188,8 +188,8 @@ def test_small_m_and_tiny_shapes_default_plan(shape):
     assert np.isnan(before).all() and np.isnan(after).all()
 
 
-@pytest.mark.parametrize("shape", [(3, 5, 7), (17, 9, 33), (65, 130, 257), (1, 1, 1), (129, 63, 100)])
-def test_unaligned_shapes_take_generic_kernel(shape):
+@pytest.mark.parametrize("shape", [(3, 5, 7), (17, 9, 33), (65, 130, 100), (1, 1, 1), (129, 63, 100)])
+def test_small_unaligned_shapes_take_generic_kernel(shape):
     M, N, K = shape
     rng = np.random.default_rng(sum(shape))
     a = wl.integers(rng, M, K, -3, 3)
@@ -301,6 +301,55 @@ def test_leading_dimensions():
         out = to_host(dC)
         assert_bit_exact(out[:, :N], ref, desc)
         assert np.isnan(out[:, N:]).all(), desc + ": wrote into the padding of C"
+
+
+@pytest.mark.parametrize("shape", [(65, 130, 257), (300, 263, 201), (129, 1001, 515), (1000, 1001, 1003), (33, 4097, 1025), (2050, 77, 130)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_unaligned_large_shapes_run_on_zero_padded_copies(shape):
+    """N or K not a multiple of 8, problem large enough: the planner pads N and K to 8 in workspace copies
+    (zero padding, Section 5.2) and runs the matrix-core kernel; results are still exact, nothing is written
+    outside C, and both B layouts agree."""
+    M, N, K = shape
+    name, a, b = wl.exact_family_for(shape, seed=13)
+    ref = orc.hgemm(a, b)
+    c, before, after, desc = run_hgemm(a, b, guard=2)
+    assert desc.startswith("mfma") and desc.endswith("pad=1"), desc
+    assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+    assert np.isnan(before).all() and np.isnan(after).all(), desc
+    c2, before, after, desc2 = run_hgemm(a, np.ascontiguousarray(b.T), b_col_major=True, guard=2)
+    assert desc2.endswith("pad=1"), desc2
+    assert_bit_exact(c2, ref, f"TN {shape} {name} {desc2}")
+    assert np.isnan(before).all() and np.isnan(after).all(), desc2
+    # real inputs, twice with the same plan: the padded copies are rewritten on every call
+    rng = np.random.default_rng(shape)
+    ar, br = wl.uniform_pm1(rng, M, K), wl.uniform_pm1(rng, K, N)
+    cr, _, _, _ = run_hgemm(ar, br)
+    assert_close(cr, orc.hgemm(ar, br), f"{shape} real {desc}")
+
+
+def test_odd_leading_dimensions_run_on_zero_padded_copies():
+    M, N, K = 264, 328, 200                      # aligned sizes, leading dimensions that are not multiples of 8
+    lda, ldb, ldc = 203, 331, 335
+    rng = np.random.default_rng(18)
+    A = wl.integers(rng, M, lda, -2, 2)
+    B = wl.integers(rng, K, ldb, -2, 2)
+    ref = orc.hgemm(np.ascontiguousarray(A[:, :K]), np.ascontiguousarray(B[:, :N]))
+    dA, dB = to_dev(A), to_dev(B)
+    dC = torch.full((M, ldc), float("nan"), dtype=torch.float16, device="cuda")
+    with hg.Plan(M, N, K, hg.Layouts.make(lda=lda, ldb=ldb, ldc=ldc)) as p:
+        desc = p.describe()
+        assert desc.endswith("pad=1"), desc
+        for _ in range(2):
+            dC.fill_(float("nan"))
+            p.run(dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            out = to_host(dC)
+            assert_bit_exact(out[:, :N], ref, desc)
+            assert np.isnan(out[:, N:]).all(), desc + ": wrote into the padding of C"
+    # an explicit matrix-core spec still refuses memory it cannot address with 16-byte copies
+    with pytest.raises(hg.HgemmError) as e:
+        hg.Plan(M, N, K, hg.Layouts.make(lda=lda, ldb=ldb, ldc=ldc), "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=1,gm=8")
+    assert e.value.status == 2
 
 
 def test_error_paths():
