@@ -119,3 +119,20 @@ def test_shapes_outside_the_table_use_the_cost_model(shape):
     ref = orc.hgemm_at(ai, bi, ii, jj)
     sel = np.abs(ref.astype(np.float64)) <= 2048
     assert np.array_equal(ci[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {name} {desc}"
+
+
+@pytest.mark.parametrize("shape", [(65536, 8, 8), (8, 65536, 8), (8, 8, 65536), (1, 8, 262144), (200000, 16, 16), (3, 100000, 40),
+                                   (1, 1000003, 8), (50000, 24, 4104)], ids=lambda s: "x".join(map(str, s)))
+def test_extreme_aspect_ratios(shape):
+    """One dimension far larger than the others (well outside the tuned table and the cost model's fitting range):
+    whatever the planner picks must still be exact on integer inputs at sampled positions and stay inside C."""
+    M, N, K = shape
+    name, a, b = wl.exact_family_for(shape, seed=21)
+    c, before, after, desc = run_hgemm(a, b, guard=1)
+    ii, jj = wl.sample_positions(shape, 4000, seed=4)
+    ref = orc.hgemm_at(a, b, ii, jj)
+    sel = np.abs(ref.astype(np.float64)) <= 2048
+    assert sel.mean() > 0.5, name
+    assert np.array_equal(c[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {name} {desc}"
+    assert np.isnan(before).all() and np.isnan(after).all(), desc
+    print(f"{shape}: {desc}")
