@@ -51,7 +51,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P"],
+                    help="C1..C5: the benchmark configurations; P: the paper's full grid, all 1000 triples over "
+                         "{64..16384}^3 (Abstract), timed shape by shape beside torch.matmul")
     ap.add_argument("--cold", action="store_true", help="rotate operand sets so caches are cold")
     ap.add_argument("--layout", default="nn", choices=["nn", "tn"],
                     help="nn: B row-major (K x N); tn: B column-major, stored N x K (Section 2.2.2)")
@@ -117,12 +119,118 @@ def cpu_baseline():
     }
 
 
+def paper_grid(args):
+    """The paper's own workload (Abstract, Section 3): every (M, N, K) in {64, ..., 16384}^3, offline mode, and
+    its headline figure -- the mean over shapes of the speedup against the vendor library -- measured here against
+    torch.matmul on the same operands.  Operands are drawn on the device (uniform[-1,1], seed per shape): a
+    thousand operand sets do not fit HBM at once, so each shape is allocated, timed and freed in turn."""
+    import numpy as np
+    import torch
+
+    import paper_2512_02551_amd as hg
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    hg.load()
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    v = wl.PAPER_GRID_VALUES
+    shapes = [(m, n, k) for m in v for n in v for k in v]
+    rows = []
+    t_wall = time.perf_counter()
+    for (M, N, K) in shapes:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(M * 1000003 + N * 1009 + K)
+        a = (torch.rand((M, K), device="cuda", generator=gen) * 2 - 1).half()
+        b = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).half()
+        c = torch.empty((M, N), device="cuda", dtype=torch.float16)
+        c_lib = torch.empty_like(c)
+        flop = 2.0 * M * N * K
+        steps = max(2, min(args.steps, int(2e12 / flop) + 2))          # a few milliseconds of work per measurement
+        warm = max(1, min(args.warmup, steps))
+        plan = hg.Plan(M, N, K)
+
+        def ours(n):
+            for _ in range(n):
+                plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+
+        def lib(n):
+            for _ in range(n):
+                torch.matmul(a, b, out=c_lib)
+
+        t = {}
+        for name, fn in (("ours", ours), ("lib", lib)):
+            fn(warm)
+            torch.cuda.synchronize()
+            replay = None
+            if args.graph:                       # both sides as graph replays: no host enqueue cost on either
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    if name == "ours":
+                        cs = torch.cuda.current_stream().cuda_stream
+                        for _ in range(steps):
+                            plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), cs)
+                    else:
+                        fn(steps)
+                replay = g.replay
+                replay()
+                torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(3):                                              # best of three batches
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                if replay:
+                    replay()
+                else:
+                    fn(steps)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) / steps)
+            t[name] = best
+        rows.append({"shape": [M, N, K], "spec": plan.describe(), "us": t["ours"] * 1e3, "tflops": flop / t["ours"] * 1e-9,
+                     "lib_us": t["lib"] * 1e3, "speedup_vs_lib": t["lib"] / t["ours"]})
+        plan.destroy()
+        del a, b, c, c_lib
+        if args.table:
+            r = rows[-1]
+            print("{:>18s} {:10.1f} us {:8.1f} TFLOP/s  torch.matmul {:10.1f} us  x{:.2f}  {}".format(
+                "x".join(map(str, r["shape"])), r["us"], r["tflops"], r["lib_us"], r["speedup_vs_lib"], r["spec"]), file=sys.stderr)
+    wall = time.perf_counter() - t_wall
+    sp = np.array([r["speedup_vs_lib"] for r in rows])
+    tf = np.array([r["tflops"] for r in rows])
+    out = {
+        "metric": "HGEMM TFLOP/s geomean over (M,N,K) grid", "value": float(np.exp(np.log(tf).mean())), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16 inputs/outputs, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "the paper's grid: 1000 triples over {64,...,16384}^3, uniform[-1,1], offline mode",
+                   "layout": "NN row-major", "cache": "warm",
+                   "timing": ("best of three replays of a graph of back-to-back calls per shape (library too)" if args.graph else
+                              "best of three batches of back-to-back calls per shape")},
+        "library_context": {
+            "what": "torch.matmul of this PyTorch build on the same operands and protocol (context only)",
+            "mean_speedup": float(sp.mean()), "geomean_speedup": float(np.exp(np.log(sp).mean())),
+            "win_rate": float((sp > 1.0).mean()), "min_speedup": float(sp.min()), "max_speedup": float(sp.max()),
+            "mean_speedup_of_max_with_library": float(np.maximum(sp, 1.0).mean()),
+        },
+        "arithmetic_mean_tflops": float(tf.mean()),
+        "per_shape": rows,
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build measures one GPU only (asked for --gpus {args.gpus}); "
               "the library has no multi-GPU path, see DESIGN.md", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "P":
+        paper_grid(args)
+        return
 
     import numpy as np
     import torch
