@@ -16,7 +16,7 @@
  *
  * Threading: functions are thread-compatible (no global mutable state apart
  * from a read-only table); a single plan must not be run on two streams at
- * once because split-K / stream-K plans own a workspace.
+ * once because split-K, stream-K and padded plans own a workspace.
  * The library never prints, never throws, never synchronises the device, and
  * launches only on the stream it is given (Section 2.4.1 forbids a kernel
  * under test from using extra streams).
