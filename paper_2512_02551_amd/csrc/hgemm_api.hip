@@ -526,7 +526,7 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
         const hgemm_layouts_t& ul = plan->ulay;
         auto copy = [&](const void* src, int64_t src_ld, int64_t src_rows, int64_t src_cols, void* dst, int64_t dst_ld, int64_t dst_rows,
                         int64_t dst_cols) {
-            const dim3 grid((unsigned)((dst_cols + 2047) / 2048),
+            const dim3 grid((unsigned)((dst_cols + kCopyColsPerBlock - 1) / kCopyColsPerBlock),
                             (unsigned)std::min<int64_t>((dst_rows + kCopyRowsPerBlock - 1) / kCopyRowsPerBlock, 32768));
             hipLaunchKernelGGL(copy2d_kernel<true>, grid, dim3(256), 0, stream, (const _Float16*)src, src_ld, src_rows, src_cols,
                                (_Float16*)dst, dst_ld, dst_rows, dst_cols);
@@ -543,7 +543,7 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     auto finish = [&]() -> hgemm_status_t {
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
         if (plan->padded) {
-            const dim3 grid((unsigned)((plan->uN + 2047) / 2048),
+            const dim3 grid((unsigned)((plan->uN + kCopyColsPerBlock - 1) / kCopyColsPerBlock),
                             (unsigned)std::min<int64_t>((plan->uM + kCopyRowsPerBlock - 1) / kCopyRowsPerBlock, 32768));
             hipLaunchKernelGGL(copy2d_kernel<false>, grid, dim3(256), 0, stream, (const _Float16*)C, N, M, N, (_Float16*)user_C,
                                plan->ulay.ldc, plan->uM, plan->uN);

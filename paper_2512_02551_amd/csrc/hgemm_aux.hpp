@@ -96,45 +96,61 @@ __global__ __launch_bounds__(256) void transpose_kernel(const _Float16* __restri
 // Pads A and B before, and copies C back after, a kernel run on zero-padded copies.  One side of every
 // such copy is a packed workspace matrix (base 256-byte aligned, columns and leading dimension multiples
 // of 8) and moves 16 bytes per lane; the caller's side may start its rows at odd element offsets and is
-// accessed two bytes at a time.  A thread handles 8 consecutive columns of kCopyRowsPerBlock rows.
+// accessed two bytes at a time.  A block handles kCopyColsPerBlock columns of kCopyRowsPerBlock rows.
 // WIDE_DST: the destination is the workspace side (padding); otherwise the source is (copy-back).
 constexpr int kCopyRowsPerBlock = 4;
+constexpr int kCopyColsPerBlock = 2048;
 template <bool WIDE_DST>
 __global__ __launch_bounds__(256) void copy2d_kernel(const _Float16* __restrict__ src, int64_t src_ld, int64_t src_rows, int64_t src_cols,
                                                      _Float16* __restrict__ dst, int64_t dst_ld, int64_t dst_rows, int64_t dst_cols)
 {
+    // The two-byte side is accessed with consecutive lanes on consecutive elements (whole cache lines per
+    // wave instruction) and the 16-byte side with 8 elements per lane; one row segment of 2048 elements
+    // changes hands through LDS in between.
     typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-    const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
-    if (c0 >= dst_cols) return;
+    __shared__ __attribute__((aligned(16))) _Float16 seg[kCopyRowsPerBlock][kCopyColsPerBlock];
+    const int t = threadIdx.x;
+    const int64_t cb = (int64_t)blockIdx.x * kCopyColsPerBlock;
     for (int64_t rb = (int64_t)blockIdx.y * kCopyRowsPerBlock; rb < dst_rows; rb += (int64_t)gridDim.y * kCopyRowsPerBlock) {
-        half8 v[kCopyRowsPerBlock];
-        // all loads of the block's rows first, then the stores: the rows are independent
+        // all rows of the block are read before any is written: 4 x 8 independent loads per lane in flight
+        if (WIDE_DST) {
 #pragma unroll
-        for (int j = 0; j < kCopyRowsPerBlock; ++j) {
-            const int64_t r = rb + j;
-            v[j] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-            if (r < src_rows && r < dst_rows) {
-                if (!WIDE_DST && c0 + 8 <= src_cols) {
-                    v[j] = *(const half8*)(src + r * src_ld + c0);
-                } else {
+            for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+                const int64_t r = rb + j;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (c0 + e < src_cols) v[j][e] = src[r * src_ld + c0 + e];
+                for (int i = 0; i < kCopyColsPerBlock / 256; ++i) {
+                    const int64_t c = cb + i * 256 + t;
+                    seg[j][i * 256 + t] = (r < src_rows && c < src_cols) ? src[r * src_ld + c] : (_Float16)0.f;
                 }
             }
-        }
+            __syncthreads();
+            const int64_t c0 = cb + t * 8;
 #pragma unroll
-        for (int j = 0; j < kCopyRowsPerBlock; ++j) {
-            const int64_t r = rb + j;
-            if (r < dst_rows) {
-                if (WIDE_DST && c0 + 8 <= dst_cols) {
-                    *(half8*)(dst + r * dst_ld + c0) = v[j];
-                } else {
+            for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+                const int64_t r = rb + j;
+                if (r < dst_rows && c0 + 8 <= dst_cols) *(half8*)(dst + r * dst_ld + c0) = *(const half8*)(&seg[j][t * 8]);
+            }
+            __syncthreads();
+        } else {
+            const int64_t c0 = cb + t * 8;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (c0 + e < dst_cols) dst[r * dst_ld + c0 + e] = v[j][e];
+            for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+                const int64_t r = rb + j;
+                half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (r < src_rows && c0 + 8 <= src_cols) v = *(const half8*)(src + r * src_ld + c0);
+                *(half8*)(&seg[j][t * 8]) = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kCopyRowsPerBlock; ++j) {
+                const int64_t r = rb + j;
+#pragma unroll
+                for (int i = 0; i < kCopyColsPerBlock / 256; ++i) {
+                    const int64_t c = cb + i * 256 + t;
+                    if (r < dst_rows && c < dst_cols) dst[r * dst_ld + c] = seg[j][i * 256 + t];
                 }
             }
+            __syncthreads();
         }
     }
 }
