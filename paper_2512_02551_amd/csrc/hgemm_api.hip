@@ -512,9 +512,9 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     if (!C) return HGEMM_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     if (K == 0) {
-        const int64_t total = M * N;
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 4096);
-        hipLaunchKernelGGL(zero_c_kernel, dim3(blocks), dim3(256), 0, stream, (_Float16*)C, M, N, plan->lay.ldc);
+        const int wide = (((uintptr_t)C & 15) == 0 && plan->lay.ldc % 8 == 0) ? 1 : 0;
+        hipLaunchKernelGGL(zero_c_kernel, dim3((unsigned)((N + 2047) / 2048), (unsigned)std::min<int64_t>(M, 16384)), dim3(256), 0, stream,
+                           (_Float16*)C, M, N, plan->lay.ldc, wide);
         return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
     }
     if (!A || !B) return HGEMM_ERR_INVALID_ARG;

@@ -155,13 +155,21 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const _Float16* __restrict_
     }
 }
 
-// C = 0 for K == 0 (the empty sum), any ldc.
-__global__ __launch_bounds__(256) void zero_c_kernel(_Float16* __restrict__ C, int64_t M, int64_t N, int64_t ldc)
+// C = 0 for K == 0 (the empty sum), any ldc.  A lane clears 8 consecutive columns: with one 16-byte
+// store where the row start and the leading dimension allow it (`wide`), else element by element.
+__global__ __launch_bounds__(256) void zero_c_kernel(_Float16* __restrict__ C, int64_t M, int64_t N, int64_t ldc, int wide)
 {
-    const int64_t total = M * N;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride)
-        C[(t / N) * ldc + (t % N)] = (_Float16)0.f;
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c0 >= N) return;
+    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int64_t r = blockIdx.y; r < M; r += gridDim.y) {
+        if (wide && c0 + 8 <= N) {
+            *(half8*)(C + r * ldc + c0) = z;
+        } else {
+            for (int e = 0; e < 8 && c0 + e < N; ++e) C[r * ldc + c0 + e] = (_Float16)0.f;
+        }
+    }
 }
 
 // Roofline calibration 1: matrix cores only.  Four independent accumulators per

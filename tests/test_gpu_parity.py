@@ -210,6 +210,15 @@ def test_empty_and_k_zero():
     b = np.zeros((0, 16), dtype=np.float16)
     c, _, _, _ = run_hgemm(a, b, prefill=7.0)
     assert c.shape == (5, 16) and not c.any()
+    # ... also for widths that are not multiples of 8 and for a padded leading dimension, touching nothing else
+    for (M, N, ldc) in [(7, 13, 13), (300, 2050, 2056), (33, 4099, 4101), (64, 4096, 4096)]:
+        dC = torch.full((M + 2, ldc), 7.0, dtype=torch.float16, device="cuda")
+        with hg.Plan(M, N, 0, hg.Layouts.make(ldc=ldc)) as p:
+            p.run(None, None, dC[1:].data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        out = to_host(dC)
+        assert not out[1:M + 1, :N].any(), (M, N, ldc)
+        assert (out[0] == 7).all() and (out[M + 1] == 7).all() and (out[1:M + 1, N:] == 7).all(), (M, N, ldc)
     # M = 0 / N = 0: nothing to do, nothing touched
     with hg.Plan(0, 16, 8) as p:
         assert p.run_status(None, None, None) == 0
