@@ -284,9 +284,13 @@ double predict_us(int64_t Mi, int64_t Ni, int64_t Ki, int bm, int bn, int bk, in
     const double epi = g.e0 + (ski > 1 ? bm * bn * 4.0 / g.BWp : bm * bn * 2.0 / g.BWepi) * 1e-3;
     const double cu_time = rounds * (kt_wg * t_kt * 1e-3 + pro + epi);
     const double tot_inflight = std::min(wgs, (double)kCUs * occ) * (double)std::max(st - 1, 1) * stage;
-    const double bw_read = (resident && part + bytes_in + bytes_c < kCacheResidentBytes) ? g.BWs : std::min(g.BWh, tot_inflight / g.Lhb);
+    const double bw_read = (resident && part + bytes_in + bytes_c < kCacheResidentBytes)
+                               ? g.BWs
+                               : std::min(g.BWh * (bn == 64 ? g.h64 : bn == 128 ? g.h128 : 1.0), tot_inflight / g.Lhb);
     const double writes = ski > 1 ? part : bytes_c;
-    const double t_main = std::max(cu_time, bytes_in / bw_read * 1e-3) + writes / (co <= 1.0 ? g.BWw1 : g.BWw2) * 1e-3;
+    const double tiles_m = (double)((Mi + bm - 1) / bm);
+    const double hbm_bytes = resident ? bytes_in : 2.0 * M * K + 2.0 * K * N * (1.0 + g.rr * (std::min(tiles_m, 8.0) - 1.0));
+    const double t_main = std::max(cu_time, hbm_bytes / bw_read * 1e-3) + writes / (co <= 1.0 ? g.BWw1 : g.BWw2) * 1e-3;
     const double t_red = ski > 1 ? g.Tr0 + g.Tr1 * std::ceil(sk / 8.0) + (part + bytes_c) / g.BWr * 1e-3 : 0.0;
     return g.T0 + t_main + t_red;
 }

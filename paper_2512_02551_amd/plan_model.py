@@ -58,6 +58,8 @@ PARAMS = {
     "BWp": 82.0,      # epilogue store rate (fp32 partial tile), bytes/ns
     "BWs": 16000.0,   # whole-chip read rate, cache-resident problems, GB/s
     "BWh": 3800.0,    # whole-chip read rate from HBM, GB/s
+    "h64": 0.6, "h128": 0.85,                   # ... scaled by BN: a workgroup reads BN*2-byte pieces of B rows (256 = 1)
+    "rr": 0.5,        # share of B that is fetched again by each further row of tiles (up to the 8 XCDs) when it does not stay cached
     "Lhb": 2500.0,    # HBM latency for the bytes-in-flight bound, ns
     "BWw1": 5400.0,   # rate at which the output (or the fp32 partials) drains when compute units hold one workgroup, GB/s
     "BWw2": 8300.0,   # ... two or more (stores of one workgroup overlap the main loop of another)
@@ -128,9 +130,11 @@ def predict_us(g: dict, D: dict):
     cu_time = rounds * (kt_wg * t_kt * 1e-3 + pro + epi)
     tot_inflight = np.minimum(wgs, CUS * occ) * np.maximum(st - 1, 1) * stage
     bw_read = np.where(resident & (part + bytes_in + bytes_c < CACHE_RESIDENT_BYTES), g["BWs"],
-                       np.minimum(g["BWh"], tot_inflight / g["Lhb"]))
+                       np.minimum(g["BWh"] * np.where(bn == 64, g["h64"], np.where(bn == 128, g["h128"], 1.0)), tot_inflight / g["Lhb"]))
     writes = np.where(sk > 1, part, bytes_c)
-    t_main = np.maximum(cu_time, bytes_in / bw_read * 1e-3) + writes / np.where(co <= 1, g["BWw1"], g["BWw2"]) * 1e-3
+    tiles_m = np.ceil(M / bm)
+    hbm_bytes = np.where(resident, bytes_in, 2.0 * M * K + 2.0 * K * N * (1.0 + g["rr"] * (np.minimum(tiles_m, 8.0) - 1.0)))
+    t_main = np.maximum(cu_time, hbm_bytes / bw_read * 1e-3) + writes / np.where(co <= 1, g["BWw1"], g["BWw2"]) * 1e-3
     t_red = np.where(sk > 1, g["Tr0"] + g["Tr1"] * np.ceil(sk / 8.0) + (part + bytes_c) / g["BWr"] * 1e-3, 0.0)
     return g["T0"] + t_main + t_red
 

@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--top", type=int, default=4)
     ap.add_argument("--table-only", action="store_true")
     ap.add_argument("--max-shapes", type=int, default=0)
+    ap.add_argument("--max-k", type=int, default=0, help="only shapes with K <= this (re-tuning a slice of a workload)")
+    ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
     ap.add_argument("--cold-workloads", default="C3",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
                          "so that the choice is made for data coming from HBM, not from the last-level cache")
@@ -119,6 +121,8 @@ def main():
 
     shapes = [s for s in all_shapes(args.workloads.split(",")) if s not in done]
     cold_shapes = set(all_shapes([w for w in args.cold_workloads.split(",") if w])) if args.cold_workloads else set()
+    if args.max_k:
+        shapes = [s for s in shapes if s[2] <= args.max_k]
     if args.max_shapes:
         shapes = shapes[:args.max_shapes]
     rng = random.Random(0)
@@ -215,7 +219,26 @@ def main():
             entry[1].destroy()
         rot["sets"] = None
         del a, b, ai, bi, c, cref
-    print("rows:", write_table(args.out_log), flush=True)
+    if args.merge_into:
+        merge_logs(args.merge_into, args.out_log)
+        print("rows:", write_table(args.merge_into), flush=True)
+    else:
+        print("rows:", write_table(args.out_log), flush=True)
+
+
+def merge_logs(main_log: str, new_log: str) -> None:
+    """Rows of new_log replace the rows of the same shapes in main_log (file order otherwise kept)."""
+    def read(path):
+        out = []
+        if os.path.exists(path):
+            with open(path) as f:
+                out = [json.loads(line) for line in f if line.strip()]
+        return out
+    new = {tuple(r["shape"]): r for r in read(new_log)}
+    rows = [new.pop(tuple(r["shape"]), r) for r in read(main_log)] + list(new.values())
+    with open(main_log, "w") as f:
+        for r in rows:
+            f.write(json.dumps(r) + "\n")
 
 
 if __name__ == "__main__":
