@@ -9,7 +9,9 @@ round, keep the best median):
   2. every candidate must first reproduce, bit for bit, the generic kernel's result on
      small-integer inputs of the same shape (exact in fp32, so any summation order agrees);
   3. a coarse pass times all survivors, a fine pass re-times the best few with more rounds; one sample
-     is the per-call time of a batch of back-to-back calls between one pair of events;
+     is the per-call time of a batch of back-to-back calls between one pair of events (for problems
+     below 2e10 flop the batch is captured in a graph and replayed, so that GPU time is compared and
+     not the host's enqueue rate);
   4. the winner and its numbers are appended to a log (so a sweep can resume) and the table is
      rewritten from the log.
 Inputs are drawn on the device; only timing and bitwise comparison happen here, all arithmetic
@@ -91,6 +93,10 @@ def main():
     ap.add_argument("--table-only", action="store_true")
     ap.add_argument("--max-shapes", type=int, default=0)
     ap.add_argument("--max-k", type=int, default=0, help="only shapes with K <= this (re-tuning a slice of a workload)")
+    ap.add_argument("--max-flop", type=float, default=0.0, help="only shapes with 2*M*N*K <= this")
+    ap.add_argument("--graph-below-flop", type=float, default=2e10,
+                    help="shapes with 2*M*N*K below this are timed as replays of a captured graph of the batch: their "
+                         "kernels are shorter than the host's enqueue time, which would otherwise hide every difference")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
     ap.add_argument("--cold-workloads", default="C3",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
@@ -123,17 +129,37 @@ def main():
     cold_shapes = set(all_shapes([w for w in args.cold_workloads.split(",") if w])) if args.cold_workloads else set()
     if args.max_k:
         shapes = [s for s in shapes if s[2] <= args.max_k]
+    if args.max_flop:
+        shapes = [s for s in shapes if 2.0 * s[0] * s[1] * s[2] <= args.max_flop]
     if args.max_shapes:
         shapes = shapes[:args.max_shapes]
     rng = random.Random(0)
     t_start = time.time()
 
-    rot = {"sets": None, "i": 0}
+    rot = {"sets": None, "i": 0, "graph": False, "graphs": {}}
 
     def timed(plan, a, b, c, rounds):
-        """One sample: `rounds` back-to-back calls between one pair of events, per-call time."""
+        """One sample: `rounds` back-to-back calls between one pair of events, per-call time.  With
+        rot["graph"] the batch is captured once per (plan, rounds) and the sample is one replay."""
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
+        if rot["graph"] and rot["sets"] is None:
+            key = (id(plan), rounds)
+            g = rot["graphs"].get(key)
+            if g is None:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    cs = torch.cuda.current_stream().cuda_stream
+                    for r in range(rounds):
+                        plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), cs)
+                rot["graphs"][key] = g
+                g.replay()
+                torch.cuda.synchronize()
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return [e0.elapsed_time(e1) / rounds]
         e0.record(stream)
         for r in range(rounds):
             if rot["sets"] is not None:
@@ -159,6 +185,8 @@ def main():
             per_set = 2 * (M * K + K * N + M * N)
             n_sets = max(2, min(64, -(-768 * 2 ** 20 // per_set)))
             rot["sets"] = [(a, b, c)] + [(a.clone(), b.clone(), torch.empty_like(c)) for _ in range(n_sets - 1)]
+        rot["graph"] = rot["sets"] is None and 2.0 * M * N * K < args.graph_below_flop
+        rot["graphs"] = {}
         gate = M * N * K <= 2 ** 37
         if gate:
             with hg.Plan(M, N, K, None, "generic") as p:
@@ -189,10 +217,14 @@ def main():
             continue
         # coarse pass, shuffled order per round group
         for entry in plans:
-            timed(entry[1], a, b, c, 2 if 2.0 * M * N * K < 2e12 else 1)
+            if not rot["graph"]:                      # a graph's first (untimed) replay is its warm-up
+                timed(entry[1], a, b, c, 2 if 2.0 * M * N * K < 2e12 else 1)
         order = list(range(len(plans)))
         rng.shuffle(order)
         coarse = args.coarse if 2.0 * M * N * K < 2e12 else max(2, args.coarse // 3)
+        fine = max(1, args.fine // 3)
+        if rot["graph"]:                              # replays are cheap and the kernels short: longer batches
+            coarse, fine = 3 * coarse, 3 * fine
         for i in order:
             plans[i][2] += timed(plans[i][1], a, b, c, coarse)
         plans.sort(key=lambda e: float(np.median(e[2])))
@@ -203,18 +235,20 @@ def main():
             order = list(range(len(best)))
             rng.shuffle(order)
             for i in order:
-                best[i][2] += timed(best[i][1], a, b, c, max(1, args.fine // 3))
+                best[i][2] += timed(best[i][1], a, b, c, fine)
         best.sort(key=lambda e: float(np.median(e[2])))
         spec, _, ts = best[0]
         med = float(np.median(ts))
         row = {"shape": [M, N, K], "spec": spec, "median_us": med * 1e3, "min_us": float(min(ts)) * 1e3,
                "tflops": 2.0 * M * N * K / med * 1e-9, "gbs": 2.0 * (M * K + K * N + M * N) / med * 1e-6,
                "candidates": len(plans), "rejected": rejected, "gated": bool(gate), "cold": rot["sets"] is not None,
+               "graph_timed": bool(rot["graph"]),
                "runner_up": [(e[0], float(np.median(e[2])) * 1e3) for e in best[1:3]]}
         with open(args.out_log, "a") as f:
             f.write(json.dumps(row) + "\n")
         print(f"[{idx + 1}/{len(shapes)}] {M}x{N}x{K}: {spec}  {row['median_us']:.1f} us  {row['tflops']:.1f} TFLOP/s  "
               f"{row['gbs']:.0f} GB/s  ({len(plans)} candidates, {rejected} rejected, {time.time() - t_start:.0f} s)", flush=True)
+        rot["graphs"] = {}
         for entry in plans:
             entry[1].destroy()
         rot["sets"] = None
