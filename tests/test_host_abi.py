@@ -72,3 +72,41 @@ def test_candidates_and_help_are_consistent(lib):
     assert "generic" in text and "mfma" in text
     skinny = hg.candidates(16, 4096, 4096)
     assert any("sk=8" in s or "sk=16" in s for s in skinny)
+
+
+# ---- randomised host-side properties ----------------------------------------------------------------
+
+from hypothesis import given, settings, strategies as hst  # noqa: E402
+
+
+@settings(max_examples=60, deadline=None)
+@given(tm=hst.integers(1, 70), tn=hst.integers(1, 70), group=hst.sampled_from([0, 1, 2, 3, 4, 8, 16, 64]))
+def test_tile_order_is_a_permutation_for_random_grids(tm, tn, group):
+    import paper_2512_02551_amd as hg
+    seen = sorted(hg.tile_of_workgroup(w, tm, tn, group) for w in range(tm * tn))
+    assert seen == list(range(tm * tn))
+    assert hg.tile_of_workgroup(tm * tn, tm, tn, group) == -1            # one past the end is refused
+
+
+@settings(max_examples=200, deadline=None)
+@given(dim=hst.integers(0, 1 << 24), tile=hst.sampled_from([8, 32, 64, 128, 160, 256]))
+def test_padding_arithmetic_properties(dim, tile):
+    import paper_2512_02551_amd as hg
+    t, p = hg.tiles(dim, tile), hg.padded(dim, tile)
+    assert p == t * tile and p >= dim and p - dim < tile
+
+
+@settings(max_examples=40, deadline=None)
+@given(M=hst.integers(1, 20000), N8=hst.integers(1, 2500), K8=hst.integers(1, 2500))
+def test_every_candidate_has_a_finite_positive_prediction(M, N8, K8):
+    """The planner takes the minimum of the cost model over these candidates, so the model has to be
+    defined (finite, positive) on every one of them, for any aligned shape."""
+    import math
+
+    import paper_2512_02551_amd as hg
+    N, K = 8 * N8, 8 * K8
+    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s]
+    assert cands and all(s.startswith("mfma,") for s in cands)
+    for s in cands[::3]:
+        us = hg.predict_us(M, N, K, s)
+        assert math.isfinite(us) and us > 1.0, (M, N, K, s, us)
