@@ -485,6 +485,12 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
                 p->spec = heuristic(M, N, K);
                 st = finish_plan(p);
             }
+            if (st != HGEMM_OK && p->padded) {       // e.g. no memory for the padded copies: the generic kernel needs none
+                p->padded = false;
+                p->M = p->uM; p->N = p->uN; p->K = p->uK; p->lay = p->ulay;
+                p->spec = Spec();
+                st = finish_plan(p);
+            }
         }
     }
     if (st != HGEMM_OK) { delete p; return st; }
