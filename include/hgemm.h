@@ -104,7 +104,9 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
 hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* C,
                          void* hip_stream);
 
-/* hgemm_destroy -- free the plan and its workspace.  NULL is accepted.      */
+/* hgemm_destroy -- free the plan and its workspace.  NULL is accepted.
+ * (Housekeeping of this interface; the paper has no passage to cite for it,
+ * nor for hgemm_status_string and hgemm_plan_describe below.)               */
 hgemm_status_t hgemm_destroy(hgemm_plan_t plan);
 
 /* ---- helpers (not on the hot path) --------------------------------------- */

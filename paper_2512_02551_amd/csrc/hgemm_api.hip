@@ -146,6 +146,23 @@ bool fast_path_ok(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l)
     return true;
 }
 
+// Compute units of the current device, asked once per process.  Host-only callers on a machine
+// without a GPU (the planner's helpers are usable there) get the MI355X figure.
+int64_t cu_count()
+{
+    static const int64_t n = [] {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+            return (int64_t)prop.multiProcessorCount;
+        (void)hipGetLastError();
+        return (int64_t)256;
+    }();
+    return n;
+}
+constexpr int64_t kLdsPerCU = 160 * 1024;
+constexpr double kCacheResidentBytes = 192.0 * 1024 * 1024;
+
 // Last-resort rules, used only when neither the table nor the cost model yields a kernel this
 // build holds.  They follow the trends of
 // Section 6 (tile height/width grow with M/N; more stages for long K) with MI355X numbers:
@@ -156,7 +173,7 @@ Spec heuristic(int64_t M, int64_t N, int64_t K)
     s.fam = FAM_MFMA;
     s.gm = 8;
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    const int CUS = 256;
+    const int64_t CUS = cu_count();
     if (M <= 32) {
         s.bm = 32; s.bn = 128; s.bk = 64; s.wm = 1; s.wn = 4; s.st = 4;
     } else if (M <= 64) {
@@ -206,9 +223,6 @@ struct PlanModel {
 const PlanModel kModel;
 
 constexpr double kPadMinMacs = 1024.0 * 1024;     // below this many multiply-adds an unaligned problem stays on the generic kernel
-constexpr int64_t kCUs = 256;
-constexpr int64_t kLdsPerCU = 160 * 1024;
-constexpr double kCacheResidentBytes = 192.0 * 1024 * 1024;
 
 // Split count finish_plan() will actually use: ranges are whole K-tiles, empty splits are dropped.
 int64_t effective_splits(int64_t ktiles, int64_t sk)
@@ -223,6 +237,7 @@ int64_t effective_splits(int64_t ktiles, int64_t sk)
 std::vector<int> split_candidates(int64_t t, int64_t ktiles)
 {
     std::vector<int> sks = {1};
+    const int64_t kCUs = cu_count();
     if (t < 2 * kCUs) {
         for (int sk : {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64}) {
             if (ktiles / sk < 2) break;
@@ -245,6 +260,7 @@ bool tile_fits_problem(const MfmaEntry& e, int64_t M, int64_t N)
 double predict_us(int64_t Mi, int64_t Ni, int64_t Ki, int bm, int bn, int bk, int wm, int wn, int st, int pf, int64_t ski)
 {
     const PlanModel& g = kModel;
+    const int64_t kCUs = cu_count();
     const double M = (double)Mi, N = (double)Ni, K = (double)Ki;
     const int nw = wm * wn;
     const double tiles = (double)(((Mi + bm - 1) / bm) * ((Ni + bn - 1) / bn));
@@ -368,9 +384,7 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     a.sk_iters_per_worker = 1;
     a.sk_total_iters = 0;
     if (s.sm) {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, p->device) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
-        const int64_t G = std::max(1, prop.multiProcessorCount);
+        const int64_t G = cu_count();
         const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
         const int64_t dp = (tiles / G) * G;
         if (dp == tiles) {
@@ -671,8 +685,8 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
 
 const char* hgemm_spec_help(void)
 {
-    static std::string text;
-    if (text.empty()) {
+    // built once, inside the initialiser of a function-local static (thread-safe since C++11)
+    static const std::string text = [] {
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
@@ -692,8 +706,8 @@ const char* hgemm_spec_help(void)
             t += b;
         }
         t += "\n";
-        text = t;
-    }
+        return t;
+    }();
     return text.c_str();
 }
 
@@ -709,7 +723,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
     if (!fast_path_ok(M, N, K, l) || M == 0 || N == 0 || K == 0) {
         out = "generic\n";
     } else {
-        const int64_t CUS = 256;
+        const int64_t CUS = cu_count();
         for (const MfmaEntry& e : registry()) {
             if (!tile_fits_problem(e, M, N)) continue;
             const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);

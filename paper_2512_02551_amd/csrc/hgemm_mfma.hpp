@@ -177,7 +177,7 @@ __device__ inline void dma16(int4v rsrc, unsigned lds_addr, unsigned voff)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)HGEMM_LDS(p); }

@@ -27,7 +27,6 @@ template <class C> inline MfmaEntry make_entry()
                      streamk_fixup_kernel<C::BM, C::BN, C::BK>};
 }
 
-void register_chunk(int chunk, std::vector<MfmaEntry>& out);    // defined in hgemm_api.hip
 void register_chunk_0(std::vector<MfmaEntry>& out);
 void register_chunk_1(std::vector<MfmaEntry>& out);
 void register_chunk_2(std::vector<MfmaEntry>& out);

@@ -37,7 +37,11 @@ def run_hgemm(a: np.ndarray, b: np.ndarray, spec=None, b_col_major=False, prefil
 def assert_close(c: np.ndarray, ref: np.ndarray, what=""):
     c64, r64 = c.astype(np.float64), ref.astype(np.float64)
     assert np.array_equal(np.isnan(c64), np.isnan(r64)), f"{what}: NaN masks differ"
-    ok = ~np.isnan(r64)
+    # an overflow (or its absence) must agree, sign included, before the finite values are compared
+    assert np.array_equal(np.isinf(c64), np.isinf(r64)), f"{what}: infinity masks differ"
+    inf = np.isinf(r64)
+    assert np.array_equal(np.sign(c64[inf]), np.sign(r64[inf])), f"{what}: infinities of opposite sign"
+    ok = ~np.isnan(r64) & ~inf
     err = np.abs(c64[ok] - r64[ok])
     bound = TOL * np.maximum(1.0, np.abs(r64[ok]))
     bad = err > bound
