@@ -181,6 +181,35 @@ def sample_positions(shape: Shape, count: int, seed: int = 0, tile: int = 256
     return np.concatenate(ii), np.concatenate(jj)
 
 
+# ---- the same distributions drawn on the device (timing runs only) --------------------
+
+def device_inputs(config: str, shape: Shape, device: str = "cuda"):
+    """(A, B) as fp16 torch tensors on ``device`` with the distribution of workload ``config``
+    ("C1".."C5"), drawn by torch's seeded generator there.  For timing runs, where a few hundred
+    operand sets would take minutes to draw on the host and the values only matter through their
+    distribution; the parity tests always use the numpy generators above, whose arrays both sides read."""
+    import torch
+
+    M, N, K = shape
+    gen = torch.Generator(device=device)
+    gen.manual_seed((int(config[1:]) * 1000003 + M) * 1000003 + N * 1009 + K)
+
+    def uniform(r, c):
+        return (torch.rand((r, c), device=device, generator=gen) * 2 - 1).half()
+
+    def gauss(r, c, std):
+        return (torch.randn((r, c), device=device, generator=gen) * std).half()
+
+    if config == "C2":
+        s = 1.0 / math.sqrt(K)
+        return gauss(M, K, s), gauss(K, N, s)
+    if config == "C3":
+        return gauss(M, K, 1.0), gauss(K, N, 0.02)
+    if config in ("C1", "C4", "C5"):
+        return uniform(M, K), uniform(K, N)
+    raise ValueError(config)
+
+
 def all_bench_shapes() -> Iterator[Tuple[str, Shape]]:
     yield "C1", C1_SHAPE
     for s in C2_SHAPES:
