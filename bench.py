@@ -1,23 +1,32 @@
 #!/usr/bin/env python3
 """HGEMM benchmark on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C1|C3|C4|C5] [--cold]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload ALL|C1|C2|C3|C4|C5|P] [--cold] ...
 
-A step is one pass of the whole hot path (plan lookup done beforehand, then hgemm_run for
-every shape of the workload) over inputs that already sit in HBM.  The default workload is
-the square sweep M=N=K in {1024, 2048, 4096, 8192} with entries N(0,1)/sqrt(K).  After W
-untimed steps, exactly K steps are timed between device synchronisations.  The K steps run
-shape-major (each shape's K calls back to back, bracketed by one pair of events on the stream
-they are launched on), which gives the per-shape times the metric is built from.  The last
-line printed is one JSON object:
+Default (no flags, workload ALL) -- the metric itself.  A step is one pass of the whole hot path
+(plans made beforehand, then one hgemm_run per shape) over every shape of
+  C4  the 200-shape grid over {64..12288}^3, uniform[-1,1]            -> `value` = geomean TFLOP/s
+  C2  the square sweep 1024^3 .. 8192^3, N(0,1)/sqrt(K)               (warm, as C4)
+  C5  16384 x 16384 x {8192, 16384}, uniform[-1,1]                    (warm)
+  C3  the 20 LLM-projection skinny shapes, A~N(0,1), B~N(0,0.02^2)    (cold: operand sets rotate
+      through > 768 MiB, so every call streams its weights from HBM)
+with all operands resident in HBM before the timed region.  After W untimed steps exactly K steps are
+timed between device synchronisations.  The K steps run shape-major: a shape's K calls go back to back
+on the stream (the paper's offline mode, Section 2.4.2) in five batches, each between its own pair of
+events on that stream (Section 2.4.1), so mean, median and minimum per-call times are real statistics
+of five measurements.  The last line printed is one JSON object:
 
-  value        geometric mean over the workload's shapes of 2*M*N*K / (mean time per call), TFLOP/s
-  roofline     the dominant kernel (largest share of the step) against the published MI355X peak
-  cpu_baseline the CPU oracle timed on a bounded sample of the same workload on this host
+  value         geometric mean over the 200 grid shapes of 2*M*N*K / (mean time per call), TFLOP/s
+  workloads     geomean and aggregate TFLOP/s of each of the four workloads
+  roofline      the dominant kernel (the launch with the largest share of a step; matrix-core bound)
+                against the published fp16 MFMA peak
+  roofline_hbm  the memory-bound skinny shapes (M <= 128 of C3, cold) against the published HBM peak:
+                best, median and count at or above 60 %
+  cpu_baseline  the CPU oracle timed on a bounded sample of the workload on this host
 
-The timing protocol follows the paper's listing in Section 2.4.1 (events around the call on the
-current stream, synchronise on both sides); "--cold" rotates through enough operand sets that
-the 256 MiB last-level cache cannot hold them (the server-mode effect of Section 2.4.2).
+With --workload C1..C5 a single workload is timed (numpy-drawn inputs, as in the parity tests);
+"--cold" rotates operand sets so that the 256 MiB last-level cache cannot hold them (the server-mode
+effect of Section 2.4.2); "--server" is server mode itself; P is the paper's 1000-shape grid.
 """
 from __future__ import annotations
 
@@ -35,10 +44,11 @@ if ROOT not in sys.path:
 PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
-# Bytes per launch between the L2s and the memory side (last-level cache + HBM) for the kernels of the
-# default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by kernels of known size
-# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); figures and commands in profiles/mfma_gemm_kernel__square_sweep.md.
-MEASURED_TRAFFIC_BYTES = {
+# Bytes per launch between the L2s and the memory side (last-level cache + HBM), NOT measured by this
+# program: copied from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program, scaled by kernels of
+# known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); figures and commands in profiles/.  Reported as
+# roofline.traffic with roofline.traffic_source saying so.
+PROFILED_TRAFFIC_BYTES = {
     (1024, 1024, 1024): (2.0 * 6185.5 + 2048.0) * 1024,
     (2048, 2048, 2048): (2.0 * 24648.4 + 8192.0) * 1024,
     (4096, 4096, 4096): (2.0 * 98382.1 + 32768.0) * 1024,
@@ -49,10 +59,11 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P"],
-                    help="C1..C5: the benchmark configurations; P: the paper's full grid, all 1000 triples over "
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="ALL", choices=["ALL", "C1", "C2", "C3", "C4", "C5", "P"],
+                    help="ALL: the metric (grid C4 as the value, C2, C5 warm and C3 cold beside it); C1..C5: one "
+                         "benchmark configuration; P: the paper's full grid, all 1000 triples over "
                          "{64..16384}^3 (Abstract), timed shape by shape beside torch.matmul")
     ap.add_argument("--cold", action="store_true", help="rotate operand sets so caches are cold")
     ap.add_argument("--layout", default="nn", choices=["nn", "tn"],
@@ -221,6 +232,160 @@ def paper_grid(args):
     print(json.dumps(out))
 
 
+def metric_run(args):
+    """The default run: the 200-shape grid (the metric's value) with the square sweep, the two large
+    shapes and the cold skinny shapes beside it, one timed region."""
+    import numpy as np
+    import torch
+
+    import paper_2512_02551_amd as hg
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    hg.load()          # fails loudly if libhgemm.so is missing: there is no fallback path
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    steps, warmup = max(1, args.steps), max(0, args.warmup)
+    n_batches = min(5, steps)
+    batch_sizes = [steps // n_batches + (1 if i < steps % n_batches else 0) for i in range(n_batches)]
+
+    jobs = [("C4", s, False) for s in wl.c4_shapes()] + [("C2", s, False) for s in wl.C2_SHAPES] + \
+           [("C5", s, False) for s in wl.C5_SHAPES] + [("C3", s, True) for s in wl.C3_SHAPES]
+    sets = []
+    for (cfg, (M, N, K), cold) in jobs:
+        a, b = wl.device_inputs(cfg, (M, N, K))
+        n_sets = 1
+        if cold:
+            per_set = 2 * (M * K + K * N + M * N)
+            n_sets = max(2, min(64, math.ceil(768 * 2 ** 20 / per_set)))
+        bufs = [(a if i == 0 else a.clone(), b if i == 0 else b.clone(), torch.empty((M, N), dtype=torch.float16, device="cuda"))
+                for i in range(n_sets)]
+        plan = hg.Plan(M, N, K, None, None)
+        sets.append({"cfg": cfg, "shape": (M, N, K), "cold": cold, "bufs": bufs, "plan": plan, "desc": plan.describe(),
+                     "info": plan.launch_info(), "next": 0})
+    torch.cuda.synchronize()
+
+    def calls(s, count):
+        bufs, plan = s["bufs"], s["plan"]
+        k0 = s["next"]
+        for k in range(count):
+            a, b, c = bufs[(k0 + k) % len(bufs)]
+            plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+        s["next"] = k0 + count
+
+    for s in sets:
+        calls(s, warmup)
+    torch.cuda.synchronize()
+
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in batch_sizes] for _ in sets]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for si, s in enumerate(sets):
+        for bi, count in enumerate(batch_sizes):
+            events[si][bi][0].record(stream)
+            calls(s, count)
+            events[si][bi][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ridge = PEAK_FP16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    per_shape = []
+    for si, s in enumerate(sets):
+        M, N, K = s["shape"]
+        flop = 2.0 * M * N * K
+        byts = 2.0 * (M * K + K * N + M * N)
+        total_ms = sum(e0.elapsed_time(e1) for (e0, e1) in events[si])
+        per_call = np.array([e0.elapsed_time(e1) / c for (e0, e1), c in zip(events[si], batch_sizes)])
+        mean_ms = total_ms / steps
+        per_shape.append({
+            "workload": s["cfg"] + (" cold" if s["cold"] else ""), "shape": [M, N, K], "spec": s["desc"],
+            "workgroups": s["info"]["workgroups"],
+            "mean_us": mean_ms * 1e3, "median_us": float(np.median(per_call)) * 1e3, "min_us": float(per_call.min()) * 1e3,
+            "tflops": flop / mean_ms * 1e-9, "gbs": byts / mean_ms * 1e-6,
+            "frac_mfma_peak": flop / mean_ms * 1e-9 / PEAK_FP16_TFLOPS,
+            "frac_hbm_peak": byts / mean_ms * 1e-6 / PEAK_HBM_GBS,
+            "ai_flop_per_byte": flop / byts,
+        })
+
+    def summary(rows):
+        fl = sum(2.0 * r["shape"][0] * r["shape"][1] * r["shape"][2] for r in rows)
+        us = sum(r["mean_us"] for r in rows)
+        return {"shapes": len(rows), "geomean_tflops": math.exp(sum(math.log(r["tflops"]) for r in rows) / len(rows)),
+                "aggregate_tflops": fl / us * 1e-6, "us_per_step": us}
+
+    groups = {}
+    for r in per_shape:
+        groups.setdefault(r["workload"], []).append(r)
+    workloads = {name: summary(rows) for name, rows in groups.items()}
+
+    # matrix-core roofline: the launch with the largest share of a step
+    dom = max(per_shape, key=lambda p: p["mean_us"])
+    M, N, K = dom["shape"]
+    roofline = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom["tflops"] / PEAK_FP16_TFLOPS, "traffic": PROFILED_TRAFFIC_BYTES.get((M, N, K)),
+                "kernel": f"{M}x{N}x{K} [{dom['spec']}]", "avg_launch_us": dom["mean_us"],
+                "flop_per_launch": 2.0 * M * N * K}
+    roofline["traffic_source"] = ("rocprofv3 FETCH_SIZE/WRITE_SIZE of an earlier run of this command, see profiles/"
+                                  if roofline["traffic"] else None)
+    assert dom["ai_flop_per_byte"] >= ridge
+    # HBM roofline: the memory-bound skinny shapes (arithmetic intensity below the ridge), streamed from HBM
+    mem = sorted((r for r in groups["C3 cold"] if r["ai_flop_per_byte"] < ridge and r["shape"][0] <= 128),
+                 key=lambda r: r["frac_hbm_peak"])
+    best, med = mem[-1], mem[len(mem) // 2]
+
+    def hbm_obj(r):
+        m, n, k = r["shape"]
+        return {"bound": "hbm", "achieved": r["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["frac_hbm_peak"],
+                "traffic": PROFILED_TRAFFIC_BYTES.get((m, n, k)), "kernel": f"{m}x{n}x{k} [{r['spec']}]",
+                "avg_launch_us": r["mean_us"], "bytes_per_launch": 2.0 * (m * k + k * n + m * n)}
+
+    roofline_hbm = hbm_obj(best)
+    roofline_hbm["median"] = hbm_obj(med)
+    roofline_hbm["memory_bound_shapes"] = len(mem)
+    roofline_hbm["at_or_above_60pct"] = sum(1 for r in mem if r["frac_hbm_peak"] >= 0.60)
+    roofline_hbm["per_shape_frac"] = {"x".join(map(str, r["shape"])): round(r["frac_hbm_peak"], 4) for r in mem}
+
+    if args.table:
+        for p in per_shape:
+            print("{:8s} {:>18s}  {:9.1f} us (median {:9.1f}, min {:9.1f})  {:8.1f} TFLOP/s ({:4.1f}% MFMA)  {:8.1f} GB/s ({:4.1f}% HBM)  {}".format(
+                p["workload"], "x".join(map(str, p["shape"])), p["mean_us"], p["median_us"], p["min_us"], p["tflops"],
+                100 * p["frac_mfma_peak"], p["gbs"], 100 * p["frac_hbm_peak"], p["spec"]), file=sys.stderr)
+
+    out = {
+        "metric": "HGEMM TFLOP/s geomean over (M,N,K) grid; % of FP16 MFMA peak / HBM BW",
+        "value": workloads["C4"]["geomean_tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 inputs/outputs, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": "C4: 200-shape grid sampled with seed 1 from {64..12288}^3, uniform[-1,1] (the value); timed in the "
+                        "same steps: C2 square sweep and C5 16384^2 x {8192,16384} warm, C3 LLM skinny shapes from HBM (cold)",
+            "layout": "NN row-major", "cache": "warm (C3: cold, rotating operand sets > 768 MiB)",
+            "timing": f"{steps} back-to-back calls per shape in {n_batches} batches, one event pair per batch on the launch stream",
+            "aggregate_tflops": sum(2.0 * r["shape"][0] * r["shape"][1] * r["shape"][2] for r in per_shape) * steps / wall * 1e-12,
+        },
+        "workloads": workloads,
+        "roofline": roofline,
+        "roofline_hbm": roofline_hbm,
+        "per_shape": per_shape,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    for s in sets:
+        s["plan"].destroy()
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -230,6 +395,13 @@ def main():
 
     if args.workload == "P":
         paper_grid(args)
+        return
+    if args.workload == "ALL":
+        if args.cold or args.server or args.graph or args.per_call_events or args.spec or args.layout != "nn" or \
+                args.library_context or args.calibrate:
+            print("bench.py: these options need a single workload (--workload C1..C5)", file=sys.stderr)
+            sys.exit(2)
+        metric_run(args)
         return
 
     import numpy as np
@@ -297,7 +469,10 @@ def main():
         run_shape(s, 0, args.warmup)
     torch.cuda.synchronize()
 
-    pair = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sets]
+    # five batches per shape, each between its own event pair: mean, median and minimum are real statistics
+    n_batches = 1 if args.graph else min(5, args.steps)
+    batch_sizes = [args.steps // n_batches + (1 if i < args.steps % n_batches else 0) for i in range(n_batches)]
+    pair = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in batch_sizes] for _ in sets]
     per_call = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
                 for _ in sets] if args.per_call_events else None
     graphs = None
@@ -315,12 +490,15 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for si, s in enumerate(sets):
-        pair[si][0].record(stream)
-        if graphs:
-            graphs[si].replay()
-        else:
-            run_shape(s, args.warmup, args.steps, per_call[si] if per_call else None)
-        pair[si][1].record(stream)
+        done = 0
+        for bi, count in enumerate(batch_sizes):
+            pair[si][bi][0].record(stream)
+            if graphs:
+                graphs[si].replay()
+            else:
+                run_shape(s, args.warmup + done, count, per_call[si][done:done + count] if per_call else None)
+            pair[si][bi][1].record(stream)
+            done += count
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -333,8 +511,9 @@ def main():
             ts = np.array([e0.elapsed_time(e1) for (e0, e1) in per_call[si]])
             mean_ms, med_ms, min_ms = float(ts.mean()), float(np.median(ts)), float(ts.min())
         else:
-            mean_ms = pair[si][0].elapsed_time(pair[si][1]) / args.steps
-            med_ms = min_ms = mean_ms
+            ts = np.array([e0.elapsed_time(e1) / c for (e0, e1), c in zip(pair[si], batch_sizes)])
+            mean_ms = float(sum(e0.elapsed_time(e1) for (e0, e1) in pair[si])) / args.steps
+            med_ms, min_ms = float(np.median(ts)), float(ts.min())
         per_shape.append({
             "shape": [M, N, K], "spec": s["desc"], "workgroups": s["info"]["workgroups"],
             "mean_us": mean_ms * 1e3, "median_us": med_ms * 1e3, "min_us": min_ms * 1e3,
@@ -356,7 +535,8 @@ def main():
     else:
         roofline = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": dom["gbs"] / PEAK_HBM_GBS}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((M, N, K))
+    roofline["traffic"] = PROFILED_TRAFFIC_BYTES.get((M, N, K))
+    roofline["traffic_source"] = "rocprofv3 counters of an earlier run of this command, see profiles/" if roofline["traffic"] else None
     roofline["kernel"] = f"{M}x{N}x{K} [{dom['spec']}]"
     roofline["avg_launch_us"] = dom["mean_us"]
 
@@ -389,7 +569,7 @@ def main():
             "timing": ("server mode: random idle gaps, per-call events" if args.server else
                        "per-call events" if args.per_call_events else
                        "replay of a HIP graph holding K back-to-back calls per shape" if args.graph else
-                       "K back-to-back calls per shape between one event pair"),
+                       f"K back-to-back calls per shape in {n_batches} batches, one event pair per batch"),
             "aggregate_tflops": total_flop * args.steps / wall * 1e-12,
         },
         "roofline": roofline,
