@@ -39,7 +39,9 @@ typedef enum {
     HGEMM_ERR_UNSUPPORTED = 2,   /* layout / leading dimension / alignment not implemented */
     HGEMM_ERR_ALLOC       = 3,   /* workspace allocation failed                            */
     HGEMM_ERR_LAUNCH      = 4,   /* the HIP runtime reported a launch error                */
-    HGEMM_ERR_ARCH        = 5    /* current device is not gfx950                           */
+    HGEMM_ERR_ARCH        = 5,   /* current device is not gfx950                           */
+    HGEMM_ERR_WORKSPACE   = 6    /* hgemm_run_static: the plan needs more scratch than the
+                                    static buffer holds                                    */
 } hgemm_status_t;
 
 typedef enum { HGEMM_ROW_MAJOR = 0, HGEMM_COL_MAJOR = 1 } hgemm_layout_t;
@@ -103,6 +105,30 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
  */
 hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* C,
                          void* hip_stream);
+
+/*
+ * hgemm_run_static -- plan and enqueue C = A*B in one call that allocates
+ * nothing, for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * argument meaning and kernels as hgemm_plan() + hgemm_run(); the difference
+ * is where the workspace lives.  Split-K planes, stream-K partial tiles and
+ * the padded copies of unaligned operands go to a static device array of
+ * HGEMM_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until
+ * the process ends) instead of a hipMalloc'ed buffer, and the plan itself
+ * lives on the call's stack.  A problem whose chosen specialisation needs more
+ * scratch than that returns HGEMM_ERR_WORKSPACE and launches nothing; problems
+ * that need no workspace are never refused.  The kernels overwrite every
+ * scratch element they later read, so nothing has to be cleared between calls.
+ * All calls on one GPU share that GPU's array: calls whose kernels may overlap
+ * in time (different streams, no dependency between them) race on it, and so
+ * does a call overlapping nothing but itself replayed concurrently from two
+ * graphs.  Calls on one stream are safe.
+ *   M,N,K,layouts   as hgemm_plan (host values); A,B,C,hip_stream as hgemm_run
+ * Errors: INVALID_ARG, UNSUPPORTED, ARCH, WORKSPACE, LAUNCH.
+ */
+#define HGEMM_STATIC_SCRATCH_BYTES (64u << 20)
+hgemm_status_t hgemm_run_static(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
+                                const void* A, const void* B, void* C, void* hip_stream);
 
 /* hgemm_destroy -- free the plan and its workspace.  NULL is accepted.
  * (Housekeeping of this interface; the paper has no passage to cite for it,

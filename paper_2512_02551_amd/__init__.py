@@ -6,5 +6,6 @@ arguments.  There is no CPU fallback: if the library is missing, import of
 """
 from .binding import (  # noqa: F401
     HgemmError, Layouts, Plan, candidates, hgemm, lib_path, load, padded, plan, predict_us, spec_help,
-    status_string, tile_of_workgroup, tiles, calibrate_mfma, calibrate_hbm_read, EXPORTS,
+    status_string, tile_of_workgroup, tiles, calibrate_mfma, calibrate_hbm_read, EXPORTS, run_static,
+    STATIC_SCRATCH_BYTES, ERR_WORKSPACE,
 )

@@ -17,8 +17,11 @@ EXPORTS = (
     "hgemm_plan", "hgemm_plan_override", "hgemm_run", "hgemm_destroy", "hgemm_status_string",
     "hgemm_plan_describe", "hgemm_plan_workspace_bytes", "hgemm_plan_launch_info", "hgemm_spec_help",
     "hgemm_candidates", "hgemm_tiles", "hgemm_padded", "hgemm_tile_of_workgroup",
-    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us",
+    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us", "hgemm_run_static",
 )
+
+STATIC_SCRATCH_BYTES = 64 << 20      # HGEMM_STATIC_SCRATCH_BYTES of include/hgemm.h
+ERR_WORKSPACE = 6
 
 ROW_MAJOR, COL_MAJOR = 0, 1
 
@@ -70,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.hgemm_plan_override.argtypes = [ctypes.POINTER(vp), i64, i64, i64, lp, cp]
     lib.hgemm_run.restype = ci
     lib.hgemm_run.argtypes = [vp, vp, vp, vp, vp]
+    lib.hgemm_run_static.restype = ci
+    lib.hgemm_run_static.argtypes = [i64, i64, i64, lp, vp, vp, vp, vp]
     lib.hgemm_destroy.restype = ci
     lib.hgemm_destroy.argtypes = [vp]
     lib.hgemm_status_string.restype = cp
@@ -207,6 +212,13 @@ class Plan:
 
     def __exit__(self, *exc):
         self.destroy()
+
+
+def run_static(M: int, N: int, K: int, layouts: Optional[Layouts], a_ptr: int, b_ptr: int, c_ptr: int, stream: int = 0) -> None:
+    """hgemm_run_static: plan and enqueue in one call that allocates nothing (static scratch workspace)."""
+    st = load().hgemm_run_static(M, N, K, ctypes.byref(layouts) if layouts is not None else None, a_ptr, b_ptr, c_ptr, stream)
+    if st != 0:
+        raise HgemmError(st, "hgemm_run_static")
 
 
 def plan(M: int, N: int, K: int, layouts: Optional[Layouts] = None, spec: Optional[str] = None) -> Plan:

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -129,9 +130,40 @@ struct hgemm_plan_s {
     hgemm_layouts_t ulay;
     size_t a_off, b_off, c_off; // byte offsets of the padded copies of A, B and C inside the workspace
     size_t bt_off;              // byte offset of the transposed copy of B (spec.tb)
+    bool static_ws;             // the workspace is this device's static scratch array, not an allocation
 };
 
+// ---------------------------------------------------------------------------
+// Static scratch for hgemm_run_static(): callers that may not allocate (code under HIP graph
+// capture, tight serving loops) get their split-K planes, stream-K partial tiles and padded operand
+// copies from this array instead of a hipMalloc'ed workspace.  Every GPU the library runs on holds
+// its own copy at its own address until the process ends.  In host code the array's name is only a
+// stand-in for the symbol: the device address comes from hipGetSymbolAddress(), once per device.
+// ---------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)HGEMM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on device `dev` (which must be the current device), or null.
+void* scratch_ptr_for(int dev)
+{
+    if (dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool fast_path_ok(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l)
 {
@@ -414,7 +446,12 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     p->bt_off = pad_bytes;
     p->partial_offset = pad_bytes + bt_bytes;
     p->workspace_bytes = pad_bytes + bt_bytes + partial_bytes;
-    if (p->workspace_bytes) {
+    if (p->workspace_bytes && p->static_ws) {
+        if (p->workspace_bytes > kScratchBytes) { p->workspace_bytes = 0; return HGEMM_ERR_WORKSPACE; }
+        p->workspace = scratch_ptr_for(p->device);
+        if (!p->workspace) { p->workspace_bytes = 0; return HGEMM_ERR_LAUNCH; }
+        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
+    } else if (p->workspace_bytes) {
         if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
             (void)hipGetLastError();
             p->workspace = nullptr;
@@ -426,10 +463,26 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     return HGEMM_OK;
 }
 
-hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
-                         const char* spec_text)
+// True when device `dev` is a gfx950; the answer is kept per device (hipGetDeviceProperties is slow).
+bool device_is_gfx950(int dev)
 {
-    if (!out) return HGEMM_ERR_INVALID_ARG;
+    static std::mutex m;
+    static signed char known[kMaxDevices] = {0};       // 0 = not asked yet, 1 = yes, -1 = no
+    if (dev < 0 || dev >= kMaxDevices) return false;
+    std::lock_guard<std::mutex> lock(m);
+    if (known[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return false; }
+        known[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    }
+    return known[dev] == 1;
+}
+
+// Fills *p (caller's storage) with a runnable plan.  static_ws: the workspace is the device's static
+// scratch array and nothing is allocated; otherwise the workspace is hipMalloc'ed and owned by the plan.
+hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, const char* spec_text,
+                         bool static_ws)
+{
     if (M < 0 || N < 0 || K < 0) return HGEMM_ERR_INVALID_ARG;
     hgemm_layouts_t l;
     if (layouts) {
@@ -450,20 +503,17 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
 
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return HGEMM_ERR_ARCH; }
-    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return HGEMM_ERR_ARCH;
+    if (!device_is_gfx950(dev)) return HGEMM_ERR_ARCH;
 
-    hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s;
-    if (!p) return HGEMM_ERR_ALLOC;
     p->M = M; p->N = N; p->K = K; p->lay = l; p->device = dev;
     p->padded = false;
+    p->static_ws = static_ws;
     p->uM = M; p->uN = N; p->uK = K; p->ulay = l;
     p->a_off = p->b_off = p->c_off = p->bt_off = 0;
 
     hgemm_status_t st;
     if (spec_text) {
-        if (!parse_spec(spec_text, &p->spec)) { delete p; return HGEMM_ERR_INVALID_ARG; }
+        if (!parse_spec(spec_text, &p->spec)) return HGEMM_ERR_INVALID_ARG;
         st = finish_plan(p);
     } else {
         bool fast = fast_path_ok(M, N, K, l) && M > 0 && N > 0 && K > 0;
@@ -499,7 +549,7 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
                 p->spec = heuristic(M, N, K);
                 st = finish_plan(p);
             }
-            if (st != HGEMM_OK && p->padded) {       // e.g. no memory for the padded copies: the generic kernel needs none
+            if (st != HGEMM_OK && st != HGEMM_ERR_WORKSPACE && p->padded) {   // e.g. no memory for the padded copies: the generic kernel needs none
                 p->padded = false;
                 p->M = p->uM; p->N = p->uN; p->K = p->uK; p->lay = p->ulay;
                 p->spec = Spec();
@@ -507,6 +557,16 @@ hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, con
             }
         }
     }
+    return st;
+}
+
+hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
+                         const char* spec_text)
+{
+    if (!out) return HGEMM_ERR_INVALID_ARG;
+    hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s;
+    if (!p) return HGEMM_ERR_ALLOC;
+    const hgemm_status_t st = init_plan(p, M, N, K, layouts, spec_text, false);
     if (st != HGEMM_OK) { delete p; return st; }
     *out = p;
     return HGEMM_OK;
@@ -528,9 +588,8 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
     return make_plan(out, M, N, K, layouts, spec);
 }
 
-hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* C, void* hip_stream)
+static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const void* B, void* C, void* hip_stream)
 {
-    if (!plan) return HGEMM_ERR_INVALID_ARG;
     const int64_t M = plan->M, N = plan->N, K = plan->K;
     if (M == 0 || N == 0) return HGEMM_OK;
     if (!C) return HGEMM_ERR_INVALID_ARG;
@@ -629,10 +688,25 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     return finish();
 }
 
+hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* C, void* hip_stream)
+{
+    if (!plan) return HGEMM_ERR_INVALID_ARG;
+    return run_plan(plan, A, B, C, hip_stream);
+}
+
+hgemm_status_t hgemm_run_static(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, const void* A, const void* B,
+                                void* C, void* hip_stream)
+{
+    hgemm_plan_s plan;                       // lives on this call's stack; its workspace is the static scratch
+    const hgemm_status_t st = init_plan(&plan, M, N, K, layouts, nullptr, true);
+    if (st != HGEMM_OK) return st;
+    return run_plan(&plan, A, B, C, hip_stream);
+}
+
 hgemm_status_t hgemm_destroy(hgemm_plan_t plan)
 {
     if (!plan) return HGEMM_OK;
-    if (plan->workspace) {
+    if (plan->workspace && !plan->static_ws) {
         if (hipFree(plan->workspace) != hipSuccess) (void)hipGetLastError();
     }
     delete plan;
@@ -648,6 +722,7 @@ const char* hgemm_status_string(hgemm_status_t status)
         case HGEMM_ERR_ALLOC: return "allocation failed";
         case HGEMM_ERR_LAUNCH: return "kernel launch failed";
         case HGEMM_ERR_ARCH: return "device is not gfx950";
+        case HGEMM_ERR_WORKSPACE: return "problem needs more scratch than the static buffer holds";
     }
     return "unknown status";
 }
