@@ -16,10 +16,11 @@ CSRC = os.path.join(_HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(_HERE, "libhgemm.so")
 HEADERS = [os.path.join(CSRC, n) for n in ("hgemm_mfma.hpp", "hgemm_aux.hpp", "hgemm_registry.hpp", "hgemm_configs.inc",
-                                           "dispatch_table.inc", "plan_model.inc")] + [os.path.join(os.path.dirname(_HERE), "include", "hgemm.h")]
+                                           "hgemm_skinny.hpp", "dispatch_table.inc", "plan_model.inc")] + [os.path.join(os.path.dirname(_HERE), "include", "hgemm.h")]
 API_SRC = os.path.join(CSRC, "hgemm_api.hip")
 KERNEL_SRC = os.path.join(CSRC, "hgemm_kernels.hip")
-DEPENDS = HEADERS + [API_SRC, KERNEL_SRC]
+SKINNY_SRC = os.path.join(CSRC, "hgemm_skinny.hip")
+DEPENDS = HEADERS + [API_SRC, KERNEL_SRC, SKINNY_SRC]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -59,7 +60,8 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 0) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     n = num_chunks()
-    tasks = [([hipcc] + HIPCC_FLAGS + ["-c", API_SRC, "-o", os.path.join(OBJ, "api.o")])]
+    tasks = [[hipcc] + HIPCC_FLAGS + ["-c", API_SRC, "-o", os.path.join(OBJ, "api.o")],
+             [hipcc] + HIPCC_FLAGS + ["-c", SKINNY_SRC, "-o", os.path.join(OBJ, "skinny.o")]]
     for k in range(n):
         tasks.append([hipcc] + HIPCC_FLAGS + [f"-DHGEMM_CHUNK={k}", "-c", KERNEL_SRC, "-o", os.path.join(OBJ, f"kernels_{k}.o")])
     jobs = jobs or min(len(tasks), max(1, min(16, os.cpu_count() or 1)))
@@ -67,7 +69,7 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 0) -> str:
         for f in [pool.submit(_run, t, verbose) for t in tasks]:
             f.result()
     tmp = LIB + f".tmp{os.getpid()}"
-    objs = [os.path.join(OBJ, "api.o")] + [os.path.join(OBJ, f"kernels_{k}.o") for k in range(n)]
+    objs = [os.path.join(OBJ, "api.o"), os.path.join(OBJ, "skinny.o")] + [os.path.join(OBJ, f"kernels_{k}.o") for k in range(n)]
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, verbose)
     os.replace(tmp, LIB)
     return LIB

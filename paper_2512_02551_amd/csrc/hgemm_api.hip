@@ -17,6 +17,7 @@
 #include "hgemm_aux.hpp"
 #include "hgemm_mfma.hpp"
 #include "hgemm_registry.hpp"
+#include "hgemm_skinny.hpp"
 
 namespace hgemm {
 
@@ -35,7 +36,11 @@ static const std::vector<MfmaEntry>& registry()
     return r;
 }
 
-enum Family { FAM_GENERIC = 0, FAM_MFMA = 1 };
+void (*skinny_kernel(int mb, bool fused))(GemmArgs);      // hgemm_skinny.hip
+
+constexpr int64_t kSkinnyMaxM = 64;
+
+enum Family { FAM_GENERIC = 0, FAM_MFMA = 1, FAM_SKINNY = 2 };
 
 struct Spec {
     Family fam = FAM_GENERIC;
@@ -45,15 +50,21 @@ struct Spec {
     int gm = 8;     // tile-order group height; 0 = row-major
     int tb = 0;     // 1 = transpose row-major B into the workspace first, then run the K-contiguous (TN) kernel
     int sm = 0;     // 1 = stream-K: whole waves of tiles data-parallel, the rest shared by K-tile iterations
+    int fr = 0;     // 1 = split-K with the reduction fused into the kernel (last-arriving workgroup sums in split order)
 };
 
 static std::string spec_to_string(const Spec& s)
 {
     char buf[160];
     if (s.fam == FAM_GENERIC) return "generic";
+    if (s.fam == FAM_SKINNY) {
+        snprintf(buf, sizeof buf, "skinny,sk=%d%s", s.sk, s.fr ? ",fr=1" : "");
+        return buf;
+    }
     snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,pf=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
              s.st, s.pf, s.sk, s.gm, s.tb ? ",tb=1" : "");
     if (s.sm) strncat(buf, ",sm=1", sizeof buf - strlen(buf) - 1);
+    if (s.fr) strncat(buf, ",fr=1", sizeof buf - strlen(buf) - 1);
     return buf;
 }
 
@@ -68,6 +79,8 @@ static bool parse_spec(const char* text, Spec* out)
         sp.fam = FAM_GENERIC;
     } else if (fam == "mfma") {
         sp.fam = FAM_MFMA;
+    } else if (fam == "skinny") {
+        sp.fam = FAM_SKINNY;
     } else {
         return false;
     }
@@ -92,10 +105,11 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "gm") sp.gm = (int)v;
         else if (key == "tb") sp.tb = (int)v;
         else if (key == "sm") sp.sm = (int)v;
+        else if (key == "fr") sp.fr = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
-    if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || (sp.sm && sp.sk > 1)) return false;
+    if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || sp.fr > 1 || (sp.sm && sp.sk > 1)) return false;
     *out = sp;
     return true;
 }
@@ -115,7 +129,8 @@ struct hgemm_plan_s {
     int64_t M, N, K;
     hgemm_layouts_t lay;        // with packed leading dimensions resolved
     Spec spec;
-    const MfmaEntry* entry;     // null for the generic family
+    const MfmaEntry* entry;     // null for the generic and skinny families
+    void (*skinny)(GemmArgs);   // the skinny family's kernel, else null
     GemmArgs args;              // pointers filled in at run time
     void* workspace;            // [transposed B (when spec.tb)] [split-K / stream-K partial sums]
     size_t workspace_bytes;
@@ -141,6 +156,7 @@ struct hgemm_plan_s {
 // stand-in for the symbol: the device address comes from hipGetSymbolAddress(), once per device.
 // ---------------------------------------------------------------------------
 constexpr size_t kScratchBytes = (size_t)HGEMM_STATIC_SCRATCH_BYTES;
+constexpr size_t kCounterBytes = 64 * 1024;      // arrival counters of fused split-K plans: up to 16384 tiles
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
@@ -343,29 +359,131 @@ double predict_us(int64_t Mi, int64_t Ni, int64_t Ki, int bm, int bn, int bk, in
     return g.T0 + t_main + t_red;
 }
 
+// Predicted microseconds of one call of a skinny-family kernel: a launch floor, the chip-wide streaming
+// time of B at a rate that grows with the number of workgroups in flight, the partial-plane traffic,
+// and the reduction (a second launch, or the tail of the fused form).
+struct SkinnyModel {
+    double t0 = 2.5;          // us: launch and first bytes
+    double bw = 5600.0;       // bytes/ns: chip-wide streaming rate with enough workgroups
+    double wg_bw = 25.0;      // bytes/ns one workgroup sustains (its two steps of loads in flight)
+    double round = 1.0;       // us of fill and drain per round of resident workgroups (3 per compute unit)
+    double part_bw = 2500.0;  // bytes/ns for writing and re-reading fp32 planes
+    double red2 = 3.2;        // us: second launch of the two-kernel reduction
+    double red1 = 2.4;        // us: tail of the fused reduction
+    double red1_per_mb = 0.9; // us more per MiB of planes when they are stored device-coherently
+};
+const SkinnyModel kSkinny;
+
+double predict_skinny_us(int64_t M, int64_t N, int64_t K, int64_t sk, bool fused)
+{
+    const SkinnyModel& g = kSkinny;
+    const double strips = (double)((N + kSkinnyCols - 1) / kSkinnyCols);
+    const double wgs = strips * (double)sk;
+    const double rate = std::min(g.bw, g.wg_bw * wgs);
+    const double planes = sk > 1 ? (double)sk * M * N * 4.0 : 0.0;
+    const double mblocks = M <= 16 ? 1.0 : M <= 32 ? 2.0 : 4.0;
+    double t = g.t0 + 2.0 * (double)K * N / rate * 1e-3 * (1.0 + 0.08 * (mblocks - 1.0)) + std::ceil(wgs / (3.0 * (double)cu_count())) * g.round +
+               2.0 * planes / g.part_bw * 1e-3;
+    if (sk > 1) t += fused ? g.red1 + g.red1_per_mb * planes / 1048576.0 : g.red2;
+    return t;
+}
+
 // The cheapest compiled configuration and split factor under the model.
-bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out)
+// Split-K with the reduction fused into the kernel against the two-launch form, as measured on skinny
+// shapes: the second launch (its dispatch gap and its own round trip) goes away, the planes are stored
+// device-coherently (slower per byte) and the last workgroup's re-read is a serial tail.
+double fused_delta_us(int64_t M, int64_t N, int64_t sk)
+{
+    const double planes_mib = (double)sk * (double)M * (double)N * 4.0 / 1048576.0;
+    return -0.8 + 1.6 * planes_mib;
+}
+
+// Slab counts worth considering for the skinny family (distinct after rounding to whole 64-row steps).
+std::vector<int> skinny_split_candidates(int64_t N, int64_t K)
+{
+    const int64_t ksteps = (K + kSkinnyStep - 1) / kSkinnyStep, strips = (N + kSkinnyCols - 1) / kSkinnyCols;
+    std::vector<int> out;
+    int64_t last = 0;
+    for (int sk : {1, 2, 4, 8, 16, 32, 64, 128}) {
+        const int64_t eff = effective_splits(ksteps, sk);
+        if (eff == last || strips * eff > 64 * cu_count()) continue;
+        last = eff;
+        out.push_back((int)eff);
+    }
+    return out;
+}
+
+bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out, bool b_row_major = true)
 {
     double best = 1e300;
     bool found = false;
+    if (b_row_major && M <= kSkinnyMaxM) {
+        for (int sk : skinny_split_candidates(N, K)) {
+            for (int fr = 0; fr <= (sk > 1 ? 1 : 0); ++fr) {
+                const double us = predict_skinny_us(M, N, K, sk, fr != 0);
+                if (us < best) {
+                    best = us;
+                    found = true;
+                    Spec s;
+                    s.fam = FAM_SKINNY; s.sk = (int)sk; s.fr = fr;
+                    *out = s;
+                }
+            }
+        }
+    }
     for (const MfmaEntry& e : registry()) {
         if (!tile_fits_problem(e, M, N)) continue;
         const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
         const int64_t ktiles = (K + e.bk - 1) / e.bk;
         for (int sk0 : split_candidates(t, ktiles)) {
             const int64_t sk = effective_splits(ktiles, sk0);
-            const double us = predict_us(M, N, K, e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf, sk);
+            double us = predict_us(M, N, K, e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf, sk);
+            const bool fuse = sk > 1 && fused_delta_us(M, N, sk) < 0.0 && (int64_t)t * (int64_t)sizeof(int) <= (int64_t)kCounterBytes;
+            if (fuse) us += fused_delta_us(M, N, sk);
             if (us < best) {
                 best = us;
                 found = true;
                 Spec s;
                 s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf;
-                s.sk = (int)sk; s.gm = 8;
+                s.sk = (int)sk; s.gm = 8; s.fr = fuse ? 1 : 0;
                 *out = s;
             }
         }
     }
     return found;
+}
+
+// Gives the plan its workspace of p->workspace_bytes (static scratch or an allocation), points the
+// partial-sum and counter arguments into it and clears the counters of an allocated one.
+hgemm_status_t acquire_workspace(hgemm_plan_s* p, size_t partial_bytes, size_t ctr_bytes)
+{
+    GemmArgs& a = p->args;
+    if (p->workspace_bytes && p->static_ws) {
+        if (p->workspace_bytes > kScratchBytes) { p->workspace_bytes = 0; return HGEMM_ERR_WORKSPACE; }
+        p->workspace = scratch_ptr_for(p->device);
+        if (!p->workspace) { p->workspace_bytes = 0; return HGEMM_ERR_LAUNCH; }
+        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
+        if (ctr_bytes) a.counters = (int*)p->workspace;          // static arrays start out zero
+    } else if (p->workspace_bytes) {
+        if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            p->workspace = nullptr;
+            p->workspace_bytes = 0;
+            return HGEMM_ERR_ALLOC;
+        }
+        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
+        if (ctr_bytes) {
+            if (hipMemset(p->workspace, 0, ctr_bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                (void)hipFree(p->workspace);
+                p->workspace = nullptr;
+                p->workspace_bytes = 0;
+                return HGEMM_ERR_ALLOC;
+            }
+            a.counters = (int*)p->workspace;
+        }
+    }
+    return HGEMM_OK;
 }
 
 hgemm_status_t finish_plan(hgemm_plan_s* p)
@@ -378,7 +496,45 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     p->partial_offset = 0;
     p->tn_kernel = false;
     memset(&p->args, 0, sizeof p->args);
+    p->skinny = nullptr;
     if (s.fam == FAM_GENERIC) return HGEMM_OK;
+    if (s.fam == FAM_SKINNY) {
+        // strips of 128 columns x K slabs of whole 64-row steps; partial planes as for split-K
+        if (p->lay.b != HGEMM_ROW_MAJOR || !fast_path_ok(M, N, K, p->lay) || M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM)
+            return HGEMM_ERR_UNSUPPORTED;
+        const int mb = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+        const int64_t ksteps = (K + kSkinnyStep - 1) / kSkinnyStep;
+        const int64_t sk = effective_splits(ksteps, s.sk);
+        if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
+        s.sk = (int)sk;
+        if (sk == 1) s.fr = 0;
+        const int64_t strips = (N + kSkinnyCols - 1) / kSkinnyCols;
+        if (s.fr && strips * (int64_t)sizeof(int) > (int64_t)kCounterBytes) return HGEMM_ERR_UNSUPPORTED;
+        p->skinny = skinny_kernel(mb, s.fr != 0);
+        if (!p->skinny) return HGEMM_ERR_UNSUPPORTED;
+        GemmArgs& a = p->args;
+        a.M = (int)M; a.N = (int)N; a.K = (int)K;
+        a.lda = (int)p->lay.lda; a.ldb = (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
+        a.tiles_m = 1; a.tiles_n = (int)strips;
+        a.splits = (int)sk;
+        a.k_per_split = (int)(((ksteps + sk - 1) / sk) * kSkinnyStep);
+        // workspace: [counters] [padded copies of A, B, C (plans on zero-padded operands)] [planes]
+        auto up256s = [](size_t b) { return ((b + 255) / 256) * 256; };
+        size_t pad_bytes = 0;
+        p->a_off = p->b_off = p->c_off = 0;
+        if (p->padded) {
+            p->b_off = up256s((size_t)M * (size_t)K * 2);
+            p->c_off = p->b_off + up256s((size_t)K * (size_t)N * 2);
+            pad_bytes = p->c_off + up256s((size_t)M * (size_t)N * 2);
+        }
+        const size_t partial_bytes = sk > 1 ? up256s((size_t)sk * (size_t)M * (size_t)N * sizeof(float)) : 0;
+        const size_t ctr_bytes = (s.fr || (p->static_ws && pad_bytes + partial_bytes > 0)) ? kCounterBytes : 0;
+        p->a_off += ctr_bytes; p->b_off += ctr_bytes; p->c_off += ctr_bytes;
+        p->bt_off = ctr_bytes + pad_bytes;
+        p->partial_offset = ctr_bytes + pad_bytes;
+        p->workspace_bytes = ctr_bytes + pad_bytes + partial_bytes;
+        return acquire_workspace(p, partial_bytes, ctr_bytes);
+    }
     const MfmaEntry* e = find_entry(s);
     if (!e) return HGEMM_ERR_UNSUPPORTED;
     if (!fast_path_ok(M, N, K, p->lay)) return HGEMM_ERR_UNSUPPORTED;
@@ -391,7 +547,9 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
         hipFuncSetAttribute((const void*)e->plain_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)e->splitk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)e->streamk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->streamk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
+        hipFuncSetAttribute((const void*)e->streamk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->splitk_fused, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->splitk_fused_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return HGEMM_ERR_LAUNCH;
     }
@@ -408,6 +566,7 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     const int64_t per = (ktiles + sk - 1) / sk;
     if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
     s.sk = (int)sk;
+    if (sk == 1) s.fr = 0;                              // nothing to reduce
     a.splits = (int)sk;
     a.k_per_split = (int)(per * e->bk);
     // stream-K geometry
@@ -443,24 +602,17 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     size_t partial_bytes = sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
     if (s.sm) partial_bytes = (size_t)2 * a.sk_workers * e->bm * e->bn * sizeof(float);
     partial_bytes = up256(partial_bytes);
-    p->bt_off = pad_bytes;
-    p->partial_offset = pad_bytes + bt_bytes;
-    p->workspace_bytes = pad_bytes + bt_bytes + partial_bytes;
-    if (p->workspace_bytes && p->static_ws) {
-        if (p->workspace_bytes > kScratchBytes) { p->workspace_bytes = 0; return HGEMM_ERR_WORKSPACE; }
-        p->workspace = scratch_ptr_for(p->device);
-        if (!p->workspace) { p->workspace_bytes = 0; return HGEMM_ERR_LAUNCH; }
-        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
-    } else if (p->workspace_bytes) {
-        if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            p->workspace = nullptr;
-            p->workspace_bytes = 0;
-            return HGEMM_ERR_ALLOC;
-        }
-        if (partial_bytes) a.partial = (float*)((char*)p->workspace + p->partial_offset);
-    }
-    return HGEMM_OK;
+    // fused split-K: one arrival counter per tile in front of everything else.  Counters are zero
+    // whenever no launch is in flight (the last arriver resets its own), so their place is fixed:
+    // the first kCounterBytes of the workspace, whatever the rest of it holds.
+    // (In the static scratch every plan keeps clear of that region, so it stays zero for the fused ones.)
+    const size_t ctr_bytes = (s.fr || (p->static_ws && pad_bytes + bt_bytes + partial_bytes > 0)) ? kCounterBytes : 0;
+    if (s.fr && (size_t)a.tiles_m * a.tiles_n * sizeof(int) > kCounterBytes) return HGEMM_ERR_UNSUPPORTED;
+    p->a_off += ctr_bytes; p->b_off += ctr_bytes; p->c_off += ctr_bytes;
+    p->bt_off = ctr_bytes + pad_bytes;
+    p->partial_offset = ctr_bytes + pad_bytes + bt_bytes;
+    p->workspace_bytes = ctr_bytes + pad_bytes + bt_bytes + partial_bytes;
+    return acquire_workspace(p, partial_bytes, ctr_bytes);
 }
 
 // True when device `dev` is a gfx950; the answer is kept per device (hipGetDeviceProperties is slow).
@@ -541,7 +693,7 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
         } else {
             const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
             if (!table_lookup(M, N, K, &p->spec) || !packed) {
-                if (!model_choice(M, N, K, &p->spec)) p->spec = heuristic(M, N, K);
+                if (!model_choice(M, N, K, &p->spec, l.b == HGEMM_ROW_MAJOR)) p->spec = heuristic(M, N, K);
             }
             if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already
             st = finish_plan(p);
@@ -658,6 +810,18 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
     a.A = (const _Float16*)A;
     a.B = (const _Float16*)B;
     a.C = (_Float16*)C;
+    if (plan->skinny) {
+        hipLaunchKernelGGL(plan->skinny, dim3((unsigned)a.tiles_n, (unsigned)a.splits), dim3(256), 0, stream, a);
+        if (a.splits > 1 && !plan->spec.fr) {
+            if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+            const int64_t quads = M * (N / 4);
+            const int blocks = (int)std::min<int64_t>((quads + 255) / 256, 2048);
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                               (const float*)((const char*)plan->workspace + plan->partial_offset), (_Float16*)C, (int)M, (int)N,
+                               (int)plan->lay.ldc, a.splits);
+        }
+        return finish();
+    }
     const MfmaEntry* e = plan->entry;
     const unsigned wgs = (unsigned)(a.tiles_m * a.tiles_n);
     if (plan->spec.tb) {
@@ -673,6 +837,9 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
         hipLaunchKernelGGL(e->fixup, dim3(wgs - (unsigned)a.dp_tiles, (unsigned)((e->bm * e->bn / 4 + 1023) / 1024)), dim3(256), 0,
                            stream, a);
+    } else if (a.splits > 1 && plan->spec.fr) {
+        hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_fused_tn : e->splitk_fused, dim3(wgs, (unsigned)a.splits), dim3(e->threads),
+                           e->lds_bytes, stream, a);
     } else if (a.splits > 1) {
         hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_tn : e->splitk, dim3(wgs, (unsigned)a.splits), dim3(e->threads), e->lds_bytes,
                            stream, a);
@@ -742,7 +909,11 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
 {
     if (!plan) return HGEMM_ERR_INVALID_ARG;
     int64_t wg, lds, th;
-    if (plan->entry) {
+    if (plan->skinny) {
+        wg = (int64_t)plan->args.tiles_n * plan->args.splits;
+        lds = kSkinnyStep * kSkinnyCols * 2;
+        th = 256;
+    } else if (plan->entry) {
         wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
                            : (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
         lds = plan->entry->lds_bytes;
@@ -765,11 +936,18 @@ const char* hgemm_spec_help(void)
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1]\n"
+            "skinny,sk=SPLITS[,fr=1]\n"
+            "    memory-bound kernel for M <= 64 rows of A (row-major B): workgroups of 4 waves take 128 columns and a\n"
+            "    K slab each and stream it in steps of 64 rows (loads one step ahead, transposed through LDS, 16x16x32\n"
+            "    matrix-core instructions with M on a 16-wide side); slabs are summed in slab order by the split-K\n"
+            "    reduction launch or, with fr = 1, inside the kernel by the workgroup that arrives last\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
             "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
             "    tb = 1: copy row-major B transposed into the workspace first and run the K-contiguous kernel,\n"
+            "    fr = 1: with sk > 1, the reduction is fused into the kernel: every workgroup stores its fp32 plane, the one\n"
+            "            that arrives last at a tile sums the planes in split order (same bits as the two-launch form)\n"
             "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
             "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
             "    pad = 1 in a description: N, K or a leading dimension is not a multiple of 8 and the kernel runs on\n"
@@ -799,6 +977,16 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
         out = "generic\n";
     } else {
         const int64_t CUS = cu_count();
+        if (l.b == HGEMM_ROW_MAJOR && M <= kSkinnyMaxM) {       // few rows: the streaming family competes
+            for (int eff : skinny_split_candidates(N, K)) {
+                for (int fr = 0; fr <= (eff > 1 ? 1 : 0); ++fr) {
+                    Spec s;
+                    s.fam = FAM_SKINNY; s.sk = (int)eff; s.fr = fr;
+                    out += spec_to_string(s);
+                    out += "\n";
+                }
+            }
+        }
         for (const MfmaEntry& e : registry()) {
             if (!tile_fits_problem(e, M, N)) continue;
             const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
@@ -817,6 +1005,12 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                     s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
+                    if (sk > 1 && gm == 8) {          // the same split with the reduction fused into the kernel
+                        s.fr = 1;
+                        out += spec_to_string(s);
+                        out += "\n";
+                        s.fr = 0;
+                    }
                     // row-major B, tall problem: paying one transposing copy of B can be cheaper than
                     // transposing reads in every workgroup
                     if (l.b == HGEMM_ROW_MAJOR && gm == 8 && M >= 1024 && e.bm >= 128 && e.bn >= 128) {
@@ -838,8 +1032,16 @@ hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spe
     if (!spec || !us || M <= 0 || N <= 0 || K <= 0) return HGEMM_ERR_INVALID_ARG;
     Spec s;
     if (!parse_spec(spec, &s)) return HGEMM_ERR_INVALID_ARG;
+    if (s.fam == FAM_SKINNY) {
+        if (M > kSkinnyMaxM) return HGEMM_ERR_UNSUPPORTED;
+        const int64_t eff = effective_splits((K + kSkinnyStep - 1) / kSkinnyStep, s.sk);
+        *us = predict_skinny_us(M, N, K, eff, s.fr != 0 && eff > 1);
+        return HGEMM_OK;
+    }
     if (s.fam != FAM_MFMA || s.sm || s.tb || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
-    *us = predict_us(M, N, K, s.bm, s.bn, s.bk, s.wm, s.wn, s.st, s.pf, effective_splits((K + s.bk - 1) / s.bk, s.sk));
+    const int64_t eff = effective_splits((K + s.bk - 1) / s.bk, s.sk);
+    *us = predict_us(M, N, K, s.bm, s.bn, s.bk, s.wm, s.wn, s.st, s.pf, eff);
+    if (s.fr && eff > 1) *us += fused_delta_us(M, N, eff);
     return HGEMM_OK;
 }
 

@@ -55,6 +55,7 @@ struct GemmArgs {
     const _Float16* B;
     _Float16* C;
     float* partial;      // split-K: [S][M][N] fp32; stream-K: partial tiles; else unused
+    int* counters;       // fused split-K: one arrival counter per output tile, zero between launches
     int M, N, K;
     int lda, ldb, ldc;   // elements
     int tiles_m, tiles_n;
@@ -69,8 +70,22 @@ struct GemmArgs {
     int sk_total_iters;  // (tiles - dp_tiles) * ceil(K / BK)
 };
 
-// Kernel modes: one full-K tile per workgroup; split-K (grid.y = split); stream-K.
-enum { MODE_PLAIN = 0, MODE_SPLITK = 1, MODE_STREAMK = 2 };
+// Kernel modes: one full-K tile per workgroup; split-K (grid.y = split) with the reduction in a
+// second launch; stream-K; split-K with the reduction fused into the kernel (the workgroup that
+// arrives last at a tile sums the planes in split order).
+enum { MODE_PLAIN = 0, MODE_SPLITK = 1, MODE_STREAMK = 2, MODE_SPLITK_FUSED = 3 };
+
+// Agent-scope relaxed atomic accesses: the compiler emits loads and stores that are coherent across
+// the whole device (the eight XCDs have private, mutually non-coherent L2 caches; plain accesses
+// would need a write-back / invalidate of a whole L2 to be seen on another XCD).
+__device__ inline void store_agent(unsigned long long* p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline unsigned long long load_agent(const unsigned long long* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // ---------------------------------------------------------------------------
 // Tile order.  Hardware deals workgroup ids round-robin to the 8 XCDs, each
@@ -169,15 +184,17 @@ __device__ inline int4v make_rsrc(const void* base, unsigned bytes)
 }
 
 // One wave-wide asynchronous copy HBM -> LDS: lane i moves 16 bytes from base + voff(i) to
-// LDS address lds_addr + 16*i (M0 carries the wave-uniform LDS base).  Issued through inline
+// LDS address lds_addr + 16*i (M0 carries the wave-uniform LDS base; it is an operand of the
+// statement, so the compiler loads it and knows it is overwritten).  Issued through inline
 // assembly on purpose: the completion of these copies is tracked by hand with vmcnt (see
-// wait_vmcnt), and the compiler must not serialise every later LDS read behind them.
+// wait_vmcnt), and the compiler must not serialise every later LDS read behind them.  The s_nop
+// is the wait state the hardware wants between a write of M0 and an LDS-direct load.
 __device__ inline void dma16(int4v rsrc, unsigned lds_addr, unsigned voff)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    asm volatile("s_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
                  :
-                 : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc)
-                 : "memory", "m0");
+                 : "v"(voff), "s"(rsrc), "{m0}"(__builtin_amdgcn_readfirstlane((int)lds_addr))
+                 : "memory");
 }
 
 __device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)HGEMM_LDS(p); }
@@ -195,7 +212,8 @@ template <class C, int MODE, bool TN>
 __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    constexpr bool SPLITK = MODE == MODE_SPLITK;
+    constexpr bool FUSED = MODE == MODE_SPLITK_FUSED;
+    constexpr bool SPLITK = MODE == MODE_SPLITK || FUSED;
     constexpr bool STREAMK = MODE == MODE_STREAMK;
 
     const int lane = threadIdx.x & 63;
@@ -493,9 +511,63 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
                     if (STREAMK) {
                         *(float4v*)(sk_slot + (row_t + tm * 32) * C::BN + col_t + tn * 32 + vg * 8) = o;
                     } else if (m < g.M && n < g.N) {
-                        *(float4v*)(g.partial + ((size_t)split * g.M + m) * g.N + n) = o;
+                        float* dst = g.partial + ((size_t)split * g.M + m) * g.N + n;
+                        if (FUSED) {
+                            // device-coherent stores: the summing workgroup may sit on another XCD
+                            union { float4v f; unsigned long long u[2]; } w;
+                            w.f = o;
+                            store_agent((unsigned long long*)dst, w.u[0]);
+                            store_agent((unsigned long long*)dst + 1, w.u[1]);
+                        } else {
+                            *(float4v*)dst = o;
+                        }
                     }
                 }
+            }
+        }
+        if (FUSED) {
+            // Fused reduction.  Every workgroup of a tile stores its fp32 plane with device-coherent
+            // stores, waits until they are performed (the release half of the barrier waits for all of
+            // the wave's outstanding stores), then counts itself in.  The workgroup that finds all
+            // others already counted -- whichever split it is -- re-reads the S planes in split order,
+            // so the sum does not depend on arrival order, rounds once and stores the tile of C.
+            // Nobody waits for anybody: a workgroup that is not last simply exits.
+            __syncthreads();
+            int* flag = (int*)lds;
+            if (threadIdx.x == 0) {
+                int* ctr = g.counters + tile_id;
+                const int arrived = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (arrived == g.splits - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // clean for the next launch
+                *flag = arrived;
+            }
+            __syncthreads();
+            if (*flag != g.splits - 1) return;
+            const int rows = min(C::BM, g.M - m0);
+            const size_t plane = (size_t)g.M * g.N;
+            constexpr int QPR = C::BN / 4;                      // groups of 4 columns per tile row
+            for (int q = threadIdx.x; q < rows * QPR; q += C::THREADS) {
+                const int m = m0 + q / QPR, n = n0 + (q % QPR) * 4;
+                if (n >= g.N) continue;
+                const unsigned long long* src = (const unsigned long long*)(g.partial + (size_t)m * g.N + n);
+                float4v sum = {0.f, 0.f, 0.f, 0.f};
+                for (int s0 = 0; s0 < g.splits; s0 += 8) {
+                    union { float4v f; unsigned long long u[2]; } v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        v[u].u[0] = v[u].u[1] = 0ull;
+                        if (s0 + u < g.splits) {
+                            v[u].u[0] = load_agent(src + (size_t)(s0 + u) * (plane / 2));
+                            v[u].u[1] = load_agent(src + (size_t)(s0 + u) * (plane / 2) + 1);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (s0 + u < g.splits) sum += v[u].f;
+                }
+                half4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
+                *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
             }
         }
     }

@@ -15,6 +15,8 @@ struct MfmaEntry {
     void (*splitk_tn)(GemmArgs);
     void (*streamk)(GemmArgs);
     void (*streamk_tn)(GemmArgs);
+    void (*splitk_fused)(GemmArgs);
+    void (*splitk_fused_tn)(GemmArgs);
     void (*fixup)(GemmArgs);
 };
 
@@ -24,6 +26,7 @@ template <class C> inline MfmaEntry make_entry()
                      mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
                      mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
                      mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
+                     mfma_gemm_kernel<C, MODE_SPLITK_FUSED, false>, mfma_gemm_kernel<C, MODE_SPLITK_FUSED, true>,
                      streamk_fixup_kernel<C::BM, C::BN, C::BK>};
 }
 

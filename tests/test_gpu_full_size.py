@@ -113,13 +113,14 @@ def test_shapes_outside_the_table_use_the_cost_model(shape):
     M, N, K = shape
     with hg.Plan(M, N, K) as p:
         chosen = p.describe()
-    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and "gm=8" in s]
+    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and ("gm=8" in s or s.startswith("skinny"))
+             and ("fr=1" not in s or s.startswith("skinny"))]
     assert hg.predict_us(M, N, K, chosen) <= min(hg.predict_us(M, N, K, s) for s in cands) * (1 + 1e-12), chosen
     rng = np.random.default_rng([M, N, K])
     a = wl.uniform_pm1(rng, M, K)
     b = wl.uniform_pm1(rng, K, N)
     c, before, after, desc = run_hgemm(a, b, guard=1)
-    assert desc.startswith("mfma"), desc
+    assert desc.startswith(("mfma", "skinny")), desc
     _check_sampled(a, b, c, 2500, f"{shape} {desc}")
     assert np.isnan(before).all() and np.isnan(after).all()
     name, ai, bi = wl.exact_family_for(shape, seed=3)

@@ -126,6 +126,116 @@ def test_split_k_bit_exact_and_ordered(sk):
         assert np.isnan(before).all() and np.isnan(after).all()
 
 
+@pytest.mark.parametrize("sk", [2, 3, 5])
+def test_fused_split_k_bit_exact_every_spec(sk):
+    """Split-K with the reduction inside the kernel (fr=1): the last-arriving workgroup of a tile sums the
+    planes in split order, so integer inputs are exact and real inputs give the bits of the two-launch form."""
+    shape = (96, 136, 1000)
+    name, a, b = wl.exact_family_for(shape, seed=2)
+    ref = orc.hgemm(a, b)
+    rng = np.random.default_rng(77)
+    ar = wl.uniform_pm1(rng, shape[0], shape[2])
+    br = wl.uniform_pm1(rng, shape[2], shape[1])
+    for spec in all_mfma_specs(sk=sk):
+        c, before, after, desc = run_hgemm(a, b, spec=spec + ",fr=1", guard=2)
+        assert "fr=1" in desc
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all()
+        two, _, _, _ = run_hgemm(ar, br, spec=spec)
+        one, _, _, _ = run_hgemm(ar, br, spec=spec + ",fr=1")
+        assert np.array_equal(one.view(np.uint16), two.view(np.uint16)), desc
+
+
+def test_fused_split_k_many_tiles_repeated_launches_and_tn():
+    """Many tiles and splits, the same plan launched again and again (the arrival counters must come back to
+    zero by themselves), ragged edges, and the column-major B layout."""
+    shape = (200, 2056, 4104)
+    name, a, b = wl.exact_family_for(shape, seed=9)
+    ii, jj = wl.sample_positions(shape, 4000, seed=7, tile=32)
+    ref = orc.hgemm_at(a, b, ii, jj).astype(np.float64)
+    sel = np.abs(ref) <= 2048
+    assert sel.mean() > 0.5
+    da, db = to_dev(a), to_dev(b)
+    dbt = to_dev(np.ascontiguousarray(b.T))
+    sh = torch.cuda.current_stream().cuda_stream
+    for spec, tn in (("mfma,bm=32,bn=64,bk=64,wm=1,wn=2,st=4,pf=3,sk=16,gm=8,fr=1", False),
+                     ("mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=7,gm=8,fr=1", False),
+                     ("mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=3,pf=3,sk=4,gm=8,fr=1", True)):
+        with hg.Plan(*shape, hg.Layouts.make(b_col_major=tn), spec) as p:
+            first = None
+            for rep in range(6):
+                c = torch.full((shape[0], shape[1]), float("nan"), dtype=torch.float16, device="cuda")
+                p.run(da.data_ptr(), (dbt if tn else db).data_ptr(), c.data_ptr(), sh)
+                torch.cuda.synchronize()
+                got = to_host(c)
+                assert np.array_equal(got[ii, jj].astype(np.float64)[sel], ref[sel]), f"{spec} launch {rep}"
+                if first is None:
+                    first = got
+                assert np.array_equal(got.view(np.uint16), first.view(np.uint16)), f"{spec} launch {rep} differs from launch 0"
+
+
+def skinny_specs(M, N, K):
+    out = [c for c in hg.candidates(M, N, K) if c.startswith("skinny")]
+    assert out
+    return out
+
+
+@pytest.mark.parametrize("shape", [(1, 264, 200), (16, 520, 1000), (7, 72, 4104), (33, 136, 328), (16, 4096, 32), (5, 8, 8), (64, 200, 776),
+                                   (48, 1032, 2056), (17, 128, 64)])
+def test_skinny_family_every_spec_bit_exact(shape):
+    """The memory-bound family (128-column strips x K slabs in steps of 64 rows, 16x16x32 matrix-core instructions,
+    slabs summed in order by the reduction launch or by the last-arriving workgroup): ragged N, K not a multiple
+    of the step or of the slab count, one, two and four 16-row blocks of A, K shorter than a step."""
+    name, a, b = wl.exact_family_for(shape, seed=12)
+    ref = orc.hgemm(a, b)
+    rng = np.random.default_rng([shape[0], shape[1], shape[2], 3])
+    ar = wl.uniform_pm1(rng, shape[0], shape[2])
+    br = wl.uniform_pm1(rng, shape[2], shape[1])
+    refr = orc.hgemm(ar, br)
+    specs = skinny_specs(*shape)
+    for spec in specs + ["skinny,sk=3", "skinny,sk=5,fr=1"]:
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=3)
+        assert desc.startswith("skinny")
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all(), f"{desc}: wrote outside C"
+        c, _, _, _ = run_hgemm(ar, br, spec=spec)
+        assert_close(c, refr, f"{shape} real {desc}")
+        again, _, _, _ = run_hgemm(ar, br, spec=spec)
+        assert np.array_equal(c.view(np.uint16), again.view(np.uint16)), f"{desc}: two runs differ"
+    # the fused reduction gives the bits of the two-launch reduction
+    two, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=4")
+    one, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=4,fr=1")
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+
+
+def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals():
+    M, N, K = 12, 328, 2056
+    name, a, b = wl.exact_family_for((M, N, K), seed=14)
+    ref = orc.hgemm(a, b)
+    lda, ldb, ldc = K + 24, N + 40, N + 8
+    A = torch.full((M, lda), float("nan"), dtype=torch.float16, device="cuda")
+    B = torch.full((K, ldb), float("nan"), dtype=torch.float16, device="cuda")
+    C = torch.full((M, ldc), float("nan"), dtype=torch.float16, device="cuda")
+    A[:, :K] = to_dev(a)
+    B[:, :N] = to_dev(b)
+    for spec in ("skinny,sk=1", "skinny,sk=4", "skinny,sk=8,fr=1"):
+        with hg.Plan(M, N, K, hg.Layouts.make(lda=lda, ldb=ldb, ldc=ldc), spec) as p:
+            for rep in range(4):            # the arrival counters of the fused form come back to zero by themselves
+                C.fill_(float("nan"))
+                p.run(A.data_ptr(), B.data_ptr(), C.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                out = to_host(C)
+                assert_bit_exact(out[:, :N], ref, f"{spec} launch {rep}")
+                assert np.isnan(out[:, N:]).all(), spec
+    # column-major B, unaligned shapes and tall A are not this family's
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(8, 64, 64, hg.Layouts.make(b_col_major=True), "skinny,sk=1")
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(8, 60, 64, None, "skinny,sk=1")
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(65, 64, 64, None, "skinny,sk=1")
+
+
 def test_every_spec_real_inputs_within_tolerance():
     shape = (520, 392, 712)
     rng = np.random.default_rng(3)

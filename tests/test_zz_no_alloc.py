@@ -22,11 +22,13 @@ def _run_static(a, b, b_col_major=False, prefill=float("nan")):
     da, db = to_dev(a), to_dev(b)
     full = torch.full((M + 2, max(N, 1)), prefill, dtype=torch.float16, device="cuda")
     c = full[1:1 + M]
+    import gc
+    gc.collect()
     before = torch.cuda.memory_allocated()
     hg.run_static(M, N, K, hg.Layouts.make(b_col_major=b_col_major), da.data_ptr(), db.data_ptr(), c.data_ptr(),
                   torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before      # nothing was taken from torch's allocator either
     out = to_host(full)
     assert np.isnan(out[0]).all() and np.isnan(out[-1]).all(), "wrote outside C"
     return out[1:1 + M, :N]
