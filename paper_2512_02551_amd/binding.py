@@ -137,7 +137,7 @@ def tile_of_workgroup(wg: int, tiles_m: int, tiles_n: int, swizzle: int) -> int:
 
 
 def candidates(M: int, N: int, K: int, layouts: Optional[Layouts] = None) -> list:
-    buf = ctypes.create_string_buffer(1 << 16)
+    buf = ctypes.create_string_buffer(1 << 19)
     st = load().hgemm_candidates(M, N, K, ctypes.byref(layouts) if layouts is not None else None, buf, len(buf))
     if st != 0:
         raise HgemmError(st, "hgemm_candidates")

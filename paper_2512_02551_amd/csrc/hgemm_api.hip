@@ -979,7 +979,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
         const int64_t CUS = cu_count();
         if (l.b == HGEMM_ROW_MAJOR && M <= kSkinnyMaxM) {       // few rows: the streaming family competes
             for (int eff : skinny_split_candidates(N, K)) {
-                for (int fr = 0; fr <= (eff > 1 ? 1 : 0); ++fr) {
+                for (int fr = 0; fr <= ((eff > 1 && fused_delta_us(M, N, eff) < 1.0) ? 1 : 0); ++fr) {
                     Spec s;
                     s.fam = FAM_SKINNY; s.sk = (int)eff; s.fr = fr;
                     out += spec_to_string(s);
@@ -1005,7 +1005,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                     s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
-                    if (sk > 1 && gm == 8) {          // the same split with the reduction fused into the kernel
+                    if (sk > 1 && gm == 8 && fused_delta_us(M, N, sk) < 1.0) {   // the same split with the reduction fused into the kernel
                         s.fr = 1;
                         out += spec_to_string(s);
                         out += "\n";

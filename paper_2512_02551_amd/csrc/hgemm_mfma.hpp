@@ -143,7 +143,11 @@ struct MfmaCfg {
     static constexpr int A_RPI = 64 / A_CPR;                           // A rows per wave-load
     static constexpr int A_RP = 256 / (BK * 2);                        // A rows per 256 B of LDS
     static constexpr int B_CPR = BN / 8;
-    static constexpr int B_RPI = 64 / B_CPR;                           // B rows per wave-load (may be 0 if BN > 512)
+    static constexpr int B_RPI = 64 / B_CPR;                           // B rows per wave-load, when a row divides a wave-load
+    // Tile widths that are not powers of two (Section 5.2: the tile need not divide the problem, nor be
+    // a power of two): a wave-load then covers a fractional number of B rows and every lane keeps one
+    // source offset per load instead of one offset plus a stride.
+    static constexpr bool B_RAGGED = 64 % B_CPR != 0;
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(KS % NSLOT == 0, "the k-steps of a tile must cycle through the fragment sets a whole number of times");
@@ -151,7 +155,8 @@ struct MfmaCfg {
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into wave loads");
     static_assert(BN >= 64 && BN <= 512, "BN");
     static_assert((NWAVES * A_RPI) % 16 == 0, "A swizzle must be periodic in the rows one round of loads covers");
-    static_assert((NWAVES * B_RPI) % 4 == 0, "B swizzle periodicity");
+    static_assert(B_RAGGED || (NWAVES * B_RPI) % 4 == 0, "B swizzle periodicity");
+    static_assert(BN % 32 == 0, "BN");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
     static_assert(LOADS * (STAGES - 1) <= 63, "vmcnt is 6 bits");
 };
@@ -163,8 +168,10 @@ template <class C> __device__ inline int swz_a(int row) { return (row / C::A_RP)
 // quarters of the 256-byte bank window.
 template <class C> __device__ inline int swz_b(int k)
 {
-    if (C::BN >= 128) return (k & 3) << 2;
-    return ((k >> 1) & 1) << 2;      // BN == 64: a row is 128 B, rows k and k+1 already differ
+    constexpr int PITCH = (C::BN * 2) % 256;      // where consecutive rows start inside the 256-byte bank window
+    if (PITCH == 0) return (k & 3) << 2;          // BN = 128, 256, 512: all four rows would start at the same place
+    if (PITCH == 128) return ((k >> 1) & 1) << 2; // BN = 64, 192: rows k and k+1 already differ, k and k+2 do not
+    return 0;                                     // BN = 96, 160: the four rows start in four different quarters
 }
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -280,6 +287,19 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const bool b_col_ok = TN ? true : (n0 + b_chunk * 8) < g.N;
     const unsigned b_voff0 = TN ? (unsigned)(((n0 + b_row) * g.ldb + k_begin + b_chunk * 8) * 2)
                                 : (b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + n0 + b_chunk * 8) * 2) : OOB);
+    // ragged B rows (NN, tile width not a power of two): 16-byte unit q*64 + lane of the tile lies in row
+    // unit / B_CPR at physical chunk unit % B_CPR, one offset per wave-load
+    constexpr bool RAGGED = !TN && C::B_RAGGED;
+    unsigned b_voffj[RAGGED ? C::B_LOADS : 1];
+    if (RAGGED) {
+#pragma unroll
+        for (int jb = 0; jb < C::B_LOADS; ++jb) {
+            const int unit = (jb * C::NWAVES + wave) * 64 + lane;
+            const int row = unit / C::B_CPR;
+            const int chunk = (unit % C::B_CPR) ^ swz_b<C>(row);
+            b_voffj[jb] = (n0 + chunk * 8) < g.N ? (unsigned)(((k_begin + row) * g.ldb + n0 + chunk * 8) * 2) : OOB;
+        }
+    }
     const unsigned b_step = TN ? (unsigned)(C::NWAVES * C::A_RPI * g.ldb * 2) : (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
     const unsigned b_kstep = TN ? (unsigned)(C::BK * 2) : (unsigned)(C::BK * g.ldb * 2);
     const int b_kcol = k_begin + b_chunk * 8;                             // TN only: + kt*BK, compared with k_end
@@ -294,9 +314,14 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
                   a_ok ? a_voff0 + (unsigned)(kt * C::BK * 2) + j * a_step : OOB);
         } else {
             const int jb = j - C::A_LOADS;
-            const bool b_ok = TN ? (b_kcol + kt * C::BK) < k_end : b_col_ok;
-            dma16(rsrcB, lds_addr_of(sB + (jb * C::NWAVES + wave) * 1024),
-                  b_ok ? b_voff0 + (unsigned)kt * b_kstep + jb * b_step : OOB);
+            if (RAGGED) {
+                dma16(rsrcB, lds_addr_of(sB + (jb * C::NWAVES + wave) * 1024),
+                      b_voffj[jb] != OOB ? b_voffj[jb] + (unsigned)kt * b_kstep : OOB);
+            } else {
+                const bool b_ok = TN ? (b_kcol + kt * C::BK) < k_end : b_col_ok;
+                dma16(rsrcB, lds_addr_of(sB + (jb * C::NWAVES + wave) * 1024),
+                      b_ok ? b_voff0 + (unsigned)kt * b_kstep + jb * b_step : OOB);
+            }
         }
     };
     auto load_tile = [&](int kt, int buf) {
