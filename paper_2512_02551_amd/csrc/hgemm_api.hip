@@ -51,6 +51,7 @@ struct Spec {
     int tb = 0;     // 1 = transpose row-major B into the workspace first, then run the K-contiguous (TN) kernel
     int sm = 0;     // 1 = stream-K: whole waves of tiles data-parallel, the rest shared by K-tile iterations
     int fr = 0;     // 1 = split-K with the reduction fused into the kernel (last-arriving workgroup sums in split order)
+    int ps = 0;     // 1 = persistent: one workgroup per compute unit walks the tiles without draining its copy pipeline
 };
 
 static std::string spec_to_string(const Spec& s)
@@ -65,6 +66,7 @@ static std::string spec_to_string(const Spec& s)
              s.st, s.pf, s.sk, s.gm, s.tb ? ",tb=1" : "");
     if (s.sm) strncat(buf, ",sm=1", sizeof buf - strlen(buf) - 1);
     if (s.fr) strncat(buf, ",fr=1", sizeof buf - strlen(buf) - 1);
+    if (s.ps) strncat(buf, ",ps=1", sizeof buf - strlen(buf) - 1);
     return buf;
 }
 
@@ -106,10 +108,12 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "tb") sp.tb = (int)v;
         else if (key == "sm") sp.sm = (int)v;
         else if (key == "fr") sp.fr = (int)v;
+        else if (key == "ps") sp.ps = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
-    if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || sp.fr > 1 || (sp.sm && sp.sk > 1)) return false;
+    if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || sp.fr > 1 || sp.ps > 1 || (sp.sm && sp.sk > 1) || (sp.ps && (sp.sk > 1 || sp.sm)))
+        return false;
     *out = sp;
     return true;
 }
@@ -549,7 +553,9 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
         hipFuncSetAttribute((const void*)e->streamk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)e->streamk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)e->splitk_fused, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk_fused_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
+        hipFuncSetAttribute((const void*)e->splitk_fused_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        (e->persist && hipFuncSetAttribute((const void*)e->persist, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ||
+        (e->persist_tn && hipFuncSetAttribute((const void*)e->persist_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess)) {
         (void)hipGetLastError();
         return HGEMM_ERR_LAUNCH;
     }
@@ -567,6 +573,11 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
     s.sk = (int)sk;
     if (sk == 1) s.fr = 0;                              // nothing to reduce
+    if (s.ps) {
+        if (!e->persist) return HGEMM_ERR_UNSUPPORTED;
+        // persistent walking needs more tiles than compute units and a K long enough to keep the pipeline full
+        if ((int64_t)a.tiles_m * a.tiles_n <= cu_count() || ktiles < e->st || sk > 1) s.ps = 0;
+    }
     a.splits = (int)sk;
     a.k_per_split = (int)(per * e->bk);
     // stream-K geometry
@@ -837,6 +848,9 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
         if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
         hipLaunchKernelGGL(e->fixup, dim3(wgs - (unsigned)a.dp_tiles, (unsigned)((e->bm * e->bn / 4 + 1023) / 1024)), dim3(256), 0,
                            stream, a);
+    } else if (plan->spec.ps) {
+        hipLaunchKernelGGL(plan->tn_kernel ? e->persist_tn : e->persist, dim3((unsigned)std::min<int64_t>(wgs, cu_count())), dim3(e->threads),
+                           e->lds_bytes, stream, a);
     } else if (a.splits > 1 && plan->spec.fr) {
         hipLaunchKernelGGL(plan->tn_kernel ? e->splitk_fused_tn : e->splitk_fused, dim3(wgs, (unsigned)a.splits), dim3(e->threads),
                            e->lds_bytes, stream, a);
@@ -916,6 +930,7 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
     } else if (plan->entry) {
         wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
                            : (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
+        if (plan->spec.ps) wg = std::min<int64_t>(wg, cu_count());
         lds = plan->entry->lds_bytes;
         th = plan->entry->threads;
     } else {
@@ -941,13 +956,15 @@ const char* hgemm_spec_help(void)
             "    K slab each and stream it in steps of 64 rows (loads one step ahead, transposed through LDS, 16x16x32\n"
             "    matrix-core instructions with M on a 16-wide side); slabs are summed in slab order by the split-K\n"
             "    reduction launch or, with fr = 1, inside the kernel by the workgroup that arrives last\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1]\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
             "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
             "    tb = 1: copy row-major B transposed into the workspace first and run the K-contiguous kernel,\n"
             "    fr = 1: with sk > 1, the reduction is fused into the kernel: every workgroup stores its fp32 plane, the one\n"
             "            that arrives last at a tile sums the planes in split order (same bits as the two-launch form)\n"
+            "    ps = 1: persistent: one workgroup per compute unit walks tiles wg, wg + grid, ...; the copies of the next\n"
+            "            tile's first K-tiles start under the last K-tiles of the current one\n"
             "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
             "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
             "    pad = 1 in a description: N, K or a leading dimension is not a multiple of 8 and the kernel runs on\n"
@@ -1005,6 +1022,12 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                     s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
+                    if (sk == 1 && gm == 8 && e.persist && t > CUS && ktiles >= e.st) {      // the same tiles walked by persistent workgroups
+                        s.ps = 1;
+                        out += spec_to_string(s);
+                        out += "\n";
+                        s.ps = 0;
+                    }
                     if (sk > 1 && gm == 8 && fused_delta_us(M, N, sk) < 1.0) {   // the same split with the reduction fused into the kernel
                         s.fr = 1;
                         out += spec_to_string(s);
@@ -1038,7 +1061,7 @@ hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spe
         *us = predict_skinny_us(M, N, K, eff, s.fr != 0 && eff > 1);
         return HGEMM_OK;
     }
-    if (s.fam != FAM_MFMA || s.sm || s.tb || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
+    if (s.fam != FAM_MFMA || s.sm || s.tb || s.ps || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
     const int64_t eff = effective_splits((K + s.bk - 1) / s.bk, s.sk);
     *us = predict_us(M, N, K, s.bm, s.bn, s.bk, s.wm, s.wn, s.st, s.pf, eff);
     if (s.fr && eff > 1) *us += fused_delta_us(M, N, eff);

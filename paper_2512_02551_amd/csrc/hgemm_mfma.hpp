@@ -72,8 +72,11 @@ struct GemmArgs {
 
 // Kernel modes: one full-K tile per workgroup; split-K (grid.y = split) with the reduction in a
 // second launch; stream-K; split-K with the reduction fused into the kernel (the workgroup that
-// arrives last at a tile sums the planes in split order).
-enum { MODE_PLAIN = 0, MODE_SPLITK = 1, MODE_STREAMK = 2, MODE_SPLITK_FUSED = 3 };
+// arrives last at a tile sums the planes in split order); persistent (one workgroup per compute unit
+// walks tiles wg, wg + grid, ... and never lets its copy pipeline drain: while the last K-tiles of a
+// tile are multiplied the first K-tiles of the next one are already being copied, and the epilogue's
+// stores complete under the next tile's main loop).
+enum { MODE_PLAIN = 0, MODE_SPLITK = 1, MODE_STREAMK = 2, MODE_SPLITK_FUSED = 3, MODE_PERSIST = 4 };
 
 // Agent-scope relaxed atomic accesses: the compiler emits loads and stores that are coherent across
 // the whole device (the eight XCDs have private, mutually non-coherent L2 caches; plain accesses
@@ -148,6 +151,8 @@ struct MfmaCfg {
     // a power of two): a wave-load then covers a fractional number of B rows and every lane keeps one
     // source offset per load instead of one offset plus a stride.
     static constexpr bool B_RAGGED = 64 % B_CPR != 0;
+    // persistent mode stages the epilogue in the one buffer the last K-tile has just vacated
+    static constexpr bool CAN_PERSIST = NWAVES * 32 * (WTN * 2 + 8) <= STAGE_BYTES;
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(KS % NSLOT == 0, "the k-steps of a tile must cycle through the fragment sets a whole number of times");
@@ -222,6 +227,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     constexpr bool FUSED = MODE == MODE_SPLITK_FUSED;
     constexpr bool SPLITK = MODE == MODE_SPLITK || FUSED;
     constexpr bool STREAMK = MODE == MODE_STREAMK;
+    constexpr bool PERSIST = MODE == MODE_PERSIST;
+    static_assert(!PERSIST || C::CAN_PERSIST, "epilogue staging must fit in one stage");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -263,9 +270,16 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         k_begin = split * g.k_per_split;
         k_end = min(g.K, k_begin + g.k_per_split);
     }
-    const int tile = (int)tile_of_workgroup(tile_id, g.tiles_m, g.tiles_n, g.swizzle);
-    const int m0 = (tile / g.tiles_n) * C::BM;
-    const int n0 = (tile % g.tiles_n) * C::BN;
+    const int total_tiles = g.tiles_m * g.tiles_n;
+    // (m0, n0): the tile being multiplied and stored.  The copies have a tile of their own (set_load_tile),
+    // which in persistent mode runs ahead of it.
+    int m0, n0;
+    auto set_tile = [&](int id) {
+        const int tile = (int)tile_of_workgroup(id, g.tiles_m, g.tiles_n, g.swizzle);
+        m0 = (tile / g.tiles_n) * C::BM;
+        n0 = (tile % g.tiles_n) * C::BN;
+    };
+    set_tile(tile_id);
     const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
 
     const unsigned OOB = 0x80000000u;        // beyond every num_records the host admits
@@ -277,29 +291,46 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // i.e. row q*A_RPI + i/A_CPR, physical chunk i%A_CPR, which must hold logical chunk p ^ swz.
     const int a_row = wave * C::A_RPI + lane / C::A_CPR;                 // + j * NWAVES*A_RPI
     const int a_chunk = (lane % C::A_CPR) ^ swz_a<C>(a_row);
-    const unsigned a_voff0 = (unsigned)(((m0 + a_row) * g.lda + k_begin + a_chunk * 8) * 2);
     const unsigned a_step = (unsigned)(C::NWAVES * C::A_RPI * g.lda * 2);
     const int a_kcol = k_begin + a_chunk * 8;                             // + kt*BK, compared with k_end
     // B, row-major (NN): wave-load q covers k-rows [q*B_RPI, (q+1)*B_RPI) of the BK x BN tile.
     // B, column-major (TN): the tile is BN x BK with K contiguous and is addressed like the A tile.
     const int b_row = TN ? wave * C::A_RPI + lane / C::A_CPR : wave * C::B_RPI + lane / C::B_CPR;
     const int b_chunk = TN ? (lane % C::A_CPR) ^ swz_a<C>(b_row) : (lane % C::B_CPR) ^ swz_b<C>(b_row);
-    const bool b_col_ok = TN ? true : (n0 + b_chunk * 8) < g.N;
-    const unsigned b_voff0 = TN ? (unsigned)(((n0 + b_row) * g.ldb + k_begin + b_chunk * 8) * 2)
-                                : (b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + n0 + b_chunk * 8) * 2) : OOB);
     // ragged B rows (NN, tile width not a power of two): 16-byte unit q*64 + lane of the tile lies in row
     // unit / B_CPR at physical chunk unit % B_CPR, one offset per wave-load
     constexpr bool RAGGED = !TN && C::B_RAGGED;
+    unsigned a_voff0, b_voff0;
+    bool b_col_ok;
     unsigned b_voffj[RAGGED ? C::B_LOADS : 1];
-    if (RAGGED) {
+    auto set_load_tile = [&](int id) {
+        if (id < 0) {                      // no tile: every copy out of range
+            a_voff0 = b_voff0 = OOB;
+            b_col_ok = true;
+            if (RAGGED) {
 #pragma unroll
-        for (int jb = 0; jb < C::B_LOADS; ++jb) {
-            const int unit = (jb * C::NWAVES + wave) * 64 + lane;
-            const int row = unit / C::B_CPR;
-            const int chunk = (unit % C::B_CPR) ^ swz_b<C>(row);
-            b_voffj[jb] = (n0 + chunk * 8) < g.N ? (unsigned)(((k_begin + row) * g.ldb + n0 + chunk * 8) * 2) : OOB;
+                for (int jb = 0; jb < C::B_LOADS; ++jb) b_voffj[jb] = OOB;
+            }
+            return;
         }
-    }
+        const int tile = (int)tile_of_workgroup(id, g.tiles_m, g.tiles_n, g.swizzle);
+        const int lm0 = (tile / g.tiles_n) * C::BM;
+        const int ln0 = (tile % g.tiles_n) * C::BN;
+        a_voff0 = (unsigned)(((lm0 + a_row) * g.lda + k_begin + a_chunk * 8) * 2);
+        b_col_ok = TN ? true : (ln0 + b_chunk * 8) < g.N;
+        b_voff0 = TN ? (unsigned)(((ln0 + b_row) * g.ldb + k_begin + b_chunk * 8) * 2)
+                     : (b_col_ok ? (unsigned)(((k_begin + b_row) * g.ldb + ln0 + b_chunk * 8) * 2) : OOB);
+        if (RAGGED) {
+#pragma unroll
+            for (int jb = 0; jb < C::B_LOADS; ++jb) {
+                const int unit = (jb * C::NWAVES + wave) * 64 + lane;
+                const int row = unit / C::B_CPR;
+                const int chunk = (unit % C::B_CPR) ^ swz_b<C>(row);
+                b_voffj[jb] = (ln0 + chunk * 8) < g.N ? (unsigned)(((k_begin + row) * g.ldb + ln0 + chunk * 8) * 2) : OOB;
+            }
+        }
+    };
+    set_load_tile(tile_id);
     const unsigned b_step = TN ? (unsigned)(C::NWAVES * C::A_RPI * g.ldb * 2) : (unsigned)(C::NWAVES * C::B_RPI * g.ldb * 2);
     const unsigned b_kstep = TN ? (unsigned)(C::BK * 2) : (unsigned)(C::BK * g.ldb * 2);
     const int b_kcol = k_begin + b_chunk * 8;                             // TN only: + kt*BK, compared with k_end
@@ -345,13 +376,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 
     half8 fa[C::NSLOT][C::TM];
     half8 fb[C::NSLOT][C::TN];
-    float16v acc[C::TM][C::TN];
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    float16v acc[C::TM][C::TN];       // zeroed at the start of every tile
 
     // Fragment read number r of a k-step: r < TM reads A fragment r, the rest read B fragment r-TM.
     constexpr int NREADS = C::TM + C::TN;
@@ -422,8 +447,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // tile kt in registers, so after the barrier buffer kt % STAGES is free for tile kt+STAGES, and
     // tile kt+1 (copies issued STAGES-1 tiles earlier) is complete and visible to all waves.
     // WAIT = number of copies that may still be in flight at the barrier; HAS_NEXT = a next tile
-    // exists; DMA = a tile kt+STAGES exists and is copied after the barrier.
-    auto tile_body = [&](int kt, int buf, int nbuf, auto wait_tag, auto has_next_tag, auto dma_tag) {
+    // exists; DMA = K-tile dma_kt (of the copies' tile) is copied into the vacated buffer after the barrier.
+    auto tile_body = [&](int dma_kt, int buf, int nbuf, auto wait_tag, auto has_next_tag, auto dma_tag) {
         constexpr int WAIT = decltype(wait_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool DMA = decltype(dma_tag)::value;
@@ -440,12 +465,14 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             const int dlo = (DMA && after) ? (j * C::LOADS) / C::PF : 0;
             const int dhi = (DMA && after) ? ((j + 1) * C::LOADS) / C::PF : 0;
             kstep(ks % C::NSLOT, in_next ? nbuf : buf, in_next ? t - C::KS : t, t % C::NSLOT, in_next ? HAS_NEXT : true,
-                  kt + C::STAGES, buf, dlo, dhi);
+                  dma_kt, buf, dlo, dhi);
         }
     };
     using std::integral_constant;
 
     // ---- main loop ----------------------------------------------------------
+    int buf = 0;                      // LDS buffer of the K-tile being multiplied
+    bool has_next = false;            // persistent mode: this workgroup has another tile after this one
     if (KT > 0) {
 #pragma unroll
         for (int s = 0; s < C::STAGES; ++s)
@@ -456,24 +483,49 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 #pragma unroll
         for (int ks = 0; ks < C::PF; ++ks) read_frags(0, ks, ks);
         __builtin_amdgcn_sched_barrier(0);
-
-        int buf = 0;
+    }
+  for (;;) {       // one pass per tile of this workgroup; a single pass unless MODE_PERSIST
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    if (KT > 0) {
+        constexpr int STEADY = (C::STAGES - 2) * C::LOADS;
         int kt = 0;
-        // steady state: a later tile exists to be copied and a next tile exists to be read
-        for (; kt + C::STAGES < KT; ++kt) {
-            const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-            tile_body(kt, buf, nbuf, integral_constant<int, (C::STAGES - 2) * C::LOADS>{}, integral_constant<bool, true>{},
-                      integral_constant<bool, true>{});
-            buf = nbuf;
+        if (PERSIST) {
+            // One loop over all K-tiles but the last, every pass with copies behind its barrier.  While
+            // this tile still has K-tiles to copy the copies are its own; from K-tile KT - STAGES on they
+            // belong to this workgroup's next tile (the pipeline does not drain).  On the workgroup's
+            // final tile those passes issue copies that are all out of range: they move nothing, and the
+            // loop keeps one shape and one count of copies in flight.  (The host admits persistent plans
+            // only when KT >= STAGES.)
+            has_next = tile_id + (int)gridDim.x < total_tiles;
+            for (; kt + 1 < KT; ++kt) {
+                const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+                if (kt + C::STAGES == KT) set_load_tile(has_next ? tile_id + (int)gridDim.x : -1);
+                tile_body(kt + C::STAGES < KT ? kt + C::STAGES : kt + C::STAGES - KT, buf, nbuf, integral_constant<int, STEADY>{},
+                          integral_constant<bool, true>{}, integral_constant<bool, true>{});
+                buf = nbuf;
+            }
+        } else {
+            // steady state: a later tile exists to be copied and a next tile exists to be read
+            for (; kt + C::STAGES < KT; ++kt) {
+                const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+                tile_body(kt + C::STAGES, buf, nbuf, integral_constant<int, STEADY>{}, integral_constant<bool, true>{},
+                          integral_constant<bool, true>{});
+                buf = nbuf;
+            }
+            // drain: no more copies to issue
+            for (; kt + 1 < KT; ++kt) {
+                const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+                tile_body(0, buf, nbuf, integral_constant<int, 0>{}, integral_constant<bool, true>{}, integral_constant<bool, false>{});
+                buf = nbuf;
+            }
         }
-        // drain: no more copies to issue
-        for (; kt + 1 < KT; ++kt) {
-            const int nbuf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
-            tile_body(kt, buf, nbuf, integral_constant<int, 0>{}, integral_constant<bool, true>{}, integral_constant<bool, false>{});
-            buf = nbuf;
-        }
-        // last tile
-        tile_body(kt, buf, buf, integral_constant<int, 0>{}, integral_constant<bool, false>{}, integral_constant<bool, false>{});
+        // last K-tile: nothing more to copy or to read ahead (persistent mode: the epilogue stages in its buffer)
+        tile_body(0, buf, buf, integral_constant<int, 0>{}, integral_constant<bool, false>{}, integral_constant<bool, false>{});
     }
 
     // ---- epilogue ------------------------------------------------------------
@@ -487,7 +539,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // all waves are done with the operand buffers
         constexpr int ROWB = C::WTN * 2 + 8;      // +8 bytes: the 32 rows a half-wave writes hit 32 different banks pairs
         constexpr int CPR = C::WTN / 8;           // 16-byte chunks per slab row
-        char* stage = lds + wave * (32 * ROWB);
+        // persistent mode: only the buffer of the last K-tile is free (the others hold the next tile's first K-tiles)
+        char* stage = lds + (PERSIST ? buf * C::STAGE_BYTES : 0) + wave * (32 * ROWB);
         static_assert(C::NWAVES * 32 * ROWB <= C::LDS_BYTES, "epilogue staging must fit in the operand buffers");
 #pragma unroll
         for (int tm = 0; tm < C::TM; ++tm) {
@@ -596,6 +649,24 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
         }
     }
+    if (PERSIST && !has_next) wait_vmcnt<0>();        // the final tile's out-of-range copies
+    if (!(PERSIST && has_next)) break;
+    // ---- persistent mode: on to this workgroup's next tile -----------------------------------
+    // The copies of its K-tiles 0 .. STAGES-2 are in flight or landed.  K-tile STAGES-1 goes into the
+    // buffer the epilogue has just staged in, once every wave has read its staging area back; then
+    // K-tile 0 must have landed (the epilogue's stores count in vmcnt too, which only makes the wait
+    // longer) and the first fragments are read, as in the prologue.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    load_tile(C::STAGES - 1, buf);
+    buf = (buf + 1 == C::STAGES) ? 0 : buf + 1;
+    wait_vmcnt<(C::STAGES - 1) * C::LOADS>();
+    asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+    for (int ks = 0; ks < C::PF; ++ks) read_frags(buf, ks, ks);
+    __builtin_amdgcn_sched_barrier(0);
+    tile_id += (int)gridDim.x;
+    set_tile(tile_id);
+  }
     if (!(STREAMK && sk_worker) || sk_iter >= sk_end) break;
     first_segment = false;
     // the next segment's copies reuse the LDS buffers: every wave must be done reading them

@@ -17,8 +17,16 @@ struct MfmaEntry {
     void (*streamk_tn)(GemmArgs);
     void (*splitk_fused)(GemmArgs);
     void (*splitk_fused_tn)(GemmArgs);
+    void (*persist)(GemmArgs);          // null when the configuration cannot stage its epilogue in one LDS buffer
+    void (*persist_tn)(GemmArgs);
     void (*fixup)(GemmArgs);
 };
+
+template <class C, bool TN> inline void (*persist_kernel())(GemmArgs)
+{
+    if constexpr (C::CAN_PERSIST) return mfma_gemm_kernel<C, MODE_PERSIST, TN>;
+    else return nullptr;
+}
 
 template <class C> inline MfmaEntry make_entry()
 {
@@ -27,6 +35,7 @@ template <class C> inline MfmaEntry make_entry()
                      mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
                      mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
                      mfma_gemm_kernel<C, MODE_SPLITK_FUSED, false>, mfma_gemm_kernel<C, MODE_SPLITK_FUSED, true>,
+                     persist_kernel<C, false>(), persist_kernel<C, true>(),
                      streamk_fixup_kernel<C::BM, C::BN, C::BK>};
 }
 

@@ -113,7 +113,7 @@ def test_shapes_outside_the_table_use_the_cost_model(shape):
     M, N, K = shape
     with hg.Plan(M, N, K) as p:
         chosen = p.describe()
-    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and ("gm=8" in s or s.startswith("skinny"))
+    cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and "ps=1" not in s and ("gm=8" in s or s.startswith("skinny"))
              and ("fr=1" not in s or s.startswith("skinny"))]
     assert hg.predict_us(M, N, K, chosen) <= min(hg.predict_us(M, N, K, s) for s in cands) * (1 + 1e-12), chosen
     rng = np.random.default_rng([M, N, K])

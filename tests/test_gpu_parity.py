@@ -174,6 +174,42 @@ def test_fused_split_k_many_tiles_repeated_launches_and_tn():
                 assert np.array_equal(got.view(np.uint16), first.view(np.uint16)), f"{spec} launch {rep} differs from launch 0"
 
 
+def test_persistent_mode_every_capable_spec_bit_exact():
+    """Persistent workgroups (ps=1): one per compute unit walks tiles wg, wg + grid, ...; the copies of the next tile
+    start under the last K-tiles of the current one and the epilogue stages in the one vacated buffer.  Ragged M and
+    N for every tile size, more tiles than compute units (up to 35 tiles per workgroup), a tile count that is not a
+    multiple of the grid, both B layouts, several tile orders."""
+    shape = (4360, 4104, 520)
+    name, a, b = wl.exact_family_for(shape, seed=31)
+    ref = orc.hgemm(a, b)
+    bt = np.ascontiguousarray(b.T)
+    ran = 0
+    for spec in all_mfma_specs():
+        try:
+            c, before, after, desc = run_hgemm(a, b, spec=spec + ",ps=1", guard=2)
+        except hg.HgemmError:
+            continue                                   # this configuration cannot stage its epilogue in one buffer
+        if "ps=1" not in desc:
+            continue                                   # too few tiles or K-tiles for this configuration
+        ran += 1
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all(), desc
+        if ran % 4 == 0:
+            c, _, _, desc = run_hgemm(a, bt, spec=spec.replace("gm=8", "gm=3") + ",ps=1", b_col_major=True)
+            assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
+    assert ran >= 30, ran
+    # real inputs, run twice: same bits; and the same bits as the non-persistent kernel (same summation order)
+    rng = np.random.default_rng(32)
+    ar = wl.uniform_pm1(rng, shape[0], shape[2])
+    br = wl.uniform_pm1(rng, shape[2], shape[1])
+    for spec in ("mfma,bm=256,bn=256,bk=64,wm=2,wn=4,st=2,pf=1,sk=1,gm=8", "mfma,bm=128,bn=128,bk=64,wm=2,wn=2,st=4,pf=3,sk=1,gm=0"):
+        plain, _, _, _ = run_hgemm(ar, br, spec=spec)
+        p1, _, _, desc = run_hgemm(ar, br, spec=spec + ",ps=1")
+        p2, _, _, _ = run_hgemm(ar, br, spec=spec + ",ps=1")
+        assert "ps=1" in desc
+        assert np.array_equal(p1.view(np.uint16), p2.view(np.uint16)) and np.array_equal(p1.view(np.uint16), plain.view(np.uint16)), desc
+
+
 def skinny_specs(M, N, K):
     out = [c for c in hg.candidates(M, N, K) if c.startswith("skinny")]
     assert out

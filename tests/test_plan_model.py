@@ -69,7 +69,7 @@ def test_predict_us_rejects_what_the_model_does_not_cover():
 
 def test_model_prefers_split_k_for_skinny_long_k_and_big_tiles_for_big_squares():
     def pick(M, N, K):
-        cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and "gm=8" in s]
+        cands = [s for s in hg.candidates(M, N, K) if "sm=1" not in s and "tb=1" not in s and "ps=1" not in s and "gm=8" in s]
         return min(cands, key=lambda s: hg.predict_us(M, N, K, s))
 
     s = pm.parse_spec(pick(16, 4096, 8192))
