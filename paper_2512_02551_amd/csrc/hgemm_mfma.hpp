@@ -124,6 +124,34 @@ __host__ __device__ inline int64_t tile_of_workgroup(int64_t wg, int64_t tiles_m
     return logical;
 }
 
+// The same map in 32-bit arithmetic for the kernels (a 64-bit division costs a few hundred cycles on
+// the GPU, and a 3 us kernel does several of them): valid while tiles_m * tiles_n < 2^31, which the
+// host checks.
+__host__ __device__ inline int tile_of_workgroup32(int wg, int tiles_m, int tiles_n, int group)
+{
+    if (group <= 0) return wg;
+    const unsigned total = (unsigned)tiles_m * (unsigned)tiles_n;
+    const unsigned XCDS = 8, WAVE = 256;
+    const unsigned uwg = (unsigned)wg;
+    const unsigned base = uwg & ~(WAVE - 1);
+    const unsigned span = (total - base < WAVE) ? (total - base) : WAVE;
+    const unsigned within = uwg - base;
+    const unsigned xcd = within % XCDS, seq = within / XCDS;
+    const unsigned q = span / XCDS, r = span % XCDS;
+    const unsigned start = xcd * q + (xcd < r ? xcd : r);
+    const unsigned logical = base + start + seq;
+    // a group taller than the grid is the whole grid (and keeps group * tiles_n inside 32 bits)
+    const unsigned ugroup = (unsigned)(group < tiles_m ? group : tiles_m), utn = (unsigned)tiles_n;
+    const unsigned band_sz = ugroup * utn;
+    const unsigned band = logical / band_sz;
+    const unsigned first_m = band * ugroup;
+    const unsigned rows = ((unsigned)tiles_m - first_m < ugroup) ? ((unsigned)tiles_m - first_m) : ugroup;
+    const unsigned in_band = logical - band * band_sz;
+    const unsigned tm = first_m + in_band % rows;
+    const unsigned tn = in_band / rows;
+    return (int)(tm * utn + tn);
+}
+
 // PF = register prefetch distance in k-steps (Sections 5.3.1 and 5.3.2: PF = 1 is the
 // double-buffered ping-pong, PF = 3 the multi-step prefetch with four fragment sets).
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int PF_ = 1>
@@ -273,13 +301,15 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int total_tiles = g.tiles_m * g.tiles_n;
     // (m0, n0): the tile being multiplied and stored.  The copies have a tile of their own (set_load_tile),
     // which in persistent mode runs ahead of it.
-    int m0, n0;
-    auto set_tile = [&](int id) {
-        const int tile = (int)tile_of_workgroup(id, g.tiles_m, g.tiles_n, g.swizzle);
-        m0 = (tile / g.tiles_n) * C::BM;
-        n0 = (tile % g.tiles_n) * C::BN;
+    int m0, n0;        // the tile being multiplied and stored
+    int lm0, ln0;      // the tile the copies read (the same one, except in persistent mode near the end of a tile)
+    auto tile_origin = [&](int id, int& tm0, int& tn0) {
+        const unsigned tile = (unsigned)tile_of_workgroup32(id, g.tiles_m, g.tiles_n, g.swizzle);
+        const unsigned tm = tile / (unsigned)g.tiles_n;
+        tm0 = (int)tm * C::BM;
+        tn0 = (int)(tile - tm * (unsigned)g.tiles_n) * C::BN;
     };
-    set_tile(tile_id);
+    tile_origin(tile_id, m0, n0);
     const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
 
     const unsigned OOB = 0x80000000u;        // beyond every num_records the host admits
@@ -313,9 +343,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
             return;
         }
-        const int tile = (int)tile_of_workgroup(id, g.tiles_m, g.tiles_n, g.swizzle);
-        const int lm0 = (tile / g.tiles_n) * C::BM;
-        const int ln0 = (tile % g.tiles_n) * C::BN;
+        if (id == tile_id) { lm0 = m0; ln0 = n0; } else tile_origin(id, lm0, ln0);
         a_voff0 = (unsigned)(((lm0 + a_row) * g.lda + k_begin + a_chunk * 8) * 2);
         b_col_ok = TN ? true : (ln0 + b_chunk * 8) < g.N;
         b_voff0 = TN ? (unsigned)(((ln0 + b_row) * g.ldb + k_begin + b_chunk * 8) * 2)
@@ -665,7 +693,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     for (int ks = 0; ks < C::PF; ++ks) read_frags(buf, ks, ks);
     __builtin_amdgcn_sched_barrier(0);
     tile_id += (int)gridDim.x;
-    set_tile(tile_id);
+    m0 = lm0;          // the copies already belong to this tile
+    n0 = ln0;
   }
     if (!(STREAMK && sk_worker) || sk_iter >= sk_end) break;
     first_segment = false;
@@ -690,7 +719,7 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmArgs g)
         const int wb = w_first * ipw, we = min(wb + ipw, g.sk_total_iters);
         if (wb <= it0 && we >= it1) return;
     }
-    const int tile = (int)tile_of_workgroup(g.dp_tiles + t, g.tiles_m, g.tiles_n, g.swizzle);
+    const int tile = tile_of_workgroup32(g.dp_tiles + t, g.tiles_m, g.tiles_n, g.swizzle);
     const int m0 = (tile / g.tiles_n) * BM;
     const int n0 = (tile % g.tiles_n) * BN;
     // blockIdx.y picks a slice of 1024 groups of 4 consecutive columns
