@@ -92,18 +92,29 @@ def main():
     ap.add_argument("--fine", type=int, default=30)
     ap.add_argument("--top", type=int, default=4)
     ap.add_argument("--table-only", action="store_true")
+    ap.add_argument("--combine", default="",
+                    help="comma-separated refinement logs (made with --candidates-from): combine them into --out-log and "
+                         "rewrite the table; no GPU work")
     ap.add_argument("--max-shapes", type=int, default=0)
     ap.add_argument("--max-k", type=int, default=0, help="only shapes with K <= this (re-tuning a slice of a workload)")
     ap.add_argument("--max-flop", type=float, default=0.0, help="only shapes with 2*M*N*K <= this")
     ap.add_argument("--graph-below-flop", type=float, default=2e10,
                     help="shapes with 2*M*N*K below this are timed as replays of a captured graph of the batch: their "
                          "kernels are shorter than the host's enqueue time, which would otherwise hide every difference")
+    ap.add_argument("--candidates-from", default="",
+                    help="comma-separated tuning logs: instead of every candidate, time only the specs these logs record "
+                         "for the shape (winners and runners-up) -- a refinement pass that settles close calls between "
+                         "earlier sweeps with many more rounds per candidate")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
     ap.add_argument("--cold-workloads", default="C3",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
                          "so that the choice is made for data coming from HBM, not from the last-level cache")
     args = ap.parse_args()
 
+    if args.combine:
+        print("rows changed:", combine_passes([p for p in args.combine.split(",") if p], args.out_log))
+        print("rows:", write_table(args.out_log))
+        return
     if args.table_only:
         print("rows:", write_table(args.out_log))
         return
@@ -136,6 +147,17 @@ def main():
         shapes = shapes[:args.max_shapes]
     rng = random.Random(0)
     t_start = time.time()
+    recorded = {}
+    for path in [p for p in args.candidates_from.split(",") if p]:
+        with open(path) as f:
+            for line in f:
+                if line.strip():
+                    r = json.loads(line)
+                    specs = recorded.setdefault(tuple(r["shape"]), [])
+                    for sp in [r["spec"]] + [x[0] for x in r.get("runner_up", [])]:
+                        sp = sp.replace(",pad=1", "")
+                        if sp and sp not in specs:
+                            specs.append(sp)
 
     rot = {"sets": None, "i": 0, "graph": False, "graphs": {}}
 
@@ -207,7 +229,7 @@ def main():
                 bands.append((r0, rows, band))
         plans = []
         rejected = 0
-        for spec in hg.candidates(M, N, K):
+        for spec in (recorded.get((M, N, K)) or hg.candidates(M, N, K)):
             try:
                 p = hg.Plan(M, N, K, None, spec)
             except hg.HgemmError:
@@ -261,6 +283,8 @@ def main():
                "candidates": len(plans), "rejected": rejected, "gated": "full" if full_gate else "row bands", "cold": rot["sets"] is not None,
                "graph_timed": bool(rot["graph"]),
                "runner_up": [(e[0], float(np.median(e[2])) * 1e3) for e in best[1:3]]}
+        if recorded.get((M, N, K)):          # refinement pass: keep every candidate's time, passes on several boxes can then be combined
+            row["all"] = [(e[0], float(np.median(e[2])) * 1e3) for e in best]
         with open(args.out_log, "a") as f:
             f.write(json.dumps(row) + "\n")
         print(f"[{idx + 1}/{len(shapes)}] {M}x{N}x{K}: {spec}  {row['median_us']:.1f} us  {row['tflops']:.1f} TFLOP/s  "
@@ -275,6 +299,52 @@ def main():
         print("rows:", write_table(args.merge_into), flush=True)
     else:
         print("rows:", write_table(args.out_log), flush=True)
+
+
+def combine_passes(paths, main_log: str) -> int:
+    """Combine refinement passes (logs whose rows carry every candidate's time, e.g. runs on several boxes): per
+    shape, the spec with the smallest median, over the passes, of time / that pass's best time; its row in
+    main_log is replaced (median time over the passes)."""
+    import statistics
+
+    def read(path):
+        with open(path) as f:
+            return {tuple(r["shape"]): r for r in (json.loads(line) for line in f if line.strip())}
+    passes = [read(p) for p in paths]
+    rows = []
+    if os.path.exists(main_log):
+        with open(main_log) as f:
+            rows = [json.loads(line) for line in f if line.strip()]
+    known = {tuple(r["shape"]) for r in rows}
+    rows += [passes[0][s] for s in passes[0] if s not in known]
+    changed = 0
+    for i, r in enumerate(rows):
+        s = tuple(r["shape"])
+        if not all(s in p and p[s].get("all") for p in passes):
+            continue
+        score = {}
+        for p in passes:
+            best = min(t for _, t in p[s]["all"])
+            for sp, t in p[s]["all"]:
+                score.setdefault(sp, []).append(t / best)
+        cand = {sp: statistics.median(v) for sp, v in score.items() if len(v) == len(passes)}
+        if not cand:
+            continue
+        sp = min(cand, key=cand.get)
+        times = lambda x: [t for p in passes for (y, t) in p[s]["all"] if y == x]
+        med = statistics.median(times(sp))
+        M, N, K = s
+        new = dict(passes[0][s])
+        new.pop("all", None)
+        new.update({"spec": sp, "median_us": med, "min_us": min(times(sp)), "tflops": 2.0 * M * N * K / med * 1e-6,
+                    "gbs": 2.0 * (M * K + K * N + M * N) / med * 1e-3, "passes": len(passes),
+                    "runner_up": sorted([(x, statistics.median(times(x))) for x in cand if x != sp], key=lambda z: z[1])[:2]})
+        changed += new["spec"] != r.get("spec")
+        rows[i] = new
+    with open(main_log, "w") as f:
+        for r in rows:
+            f.write(json.dumps(r) + "\n")
+    return changed
 
 
 def merge_logs(main_log: str, new_log: str) -> None:
