@@ -14,7 +14,8 @@ with all operands resident in HBM before the timed region.  After W untimed step
 timed between device synchronisations.  The K steps run shape-major: a shape's K calls go back to back
 on the stream (the paper's offline mode, Section 2.4.2) in five batches, each between its own pair of
 events on that stream (Section 2.4.1), so mean, median and minimum per-call times are real statistics
-of five measurements.  The last line printed is one JSON object:
+of five measurements.  With --graph each batch is captured once in a HIP graph and replayed instead
+(no host enqueue cost; pays only with long batches).  The last line printed is one JSON object:
 
   value         geometric mean over the 200 grid shapes of 2*M*N*K / (mean time per call), TFLOP/s
   workloads     geomean and aggregate TFLOP/s of each of the four workloads
@@ -249,7 +250,10 @@ def metric_run(args):
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
     steps, warmup = max(1, args.steps), max(0, args.warmup)
-    n_batches = min(5, steps)
+    # An event record between batches costs the stream about 4 us (measured: 3.4 us per call of a 2.4 us
+    # kernel in batches of 4, 2.8 in batches of 10), so a batch holds at least 10 calls; with fewer than
+    # five batches per shape the median and minimum are not reported.
+    n_batches = min(5, max(1, steps // 10))
     batch_sizes = [steps // n_batches + (1 if i < steps % n_batches else 0) for i in range(n_batches)]
 
     jobs = [("C4", s, False) for s in wl.c4_shapes()] + [("C2", s, False) for s in wl.C2_SHAPES] + \
@@ -268,28 +272,60 @@ def metric_run(args):
                      "info": plan.launch_info(), "next": 0})
     torch.cuda.synchronize()
 
-    def calls(s, count):
-        bufs, plan = s["bufs"], s["plan"]
-        k0 = s["next"]
-        for k in range(count):
-            a, b, c = bufs[(k0 + k) % len(bufs)]
-            plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+    # The enqueue loop is kept as thin as Python allows (entry point bound once, device pointers taken once):
+    # the 2-3 us kernels of the small grid shapes are otherwise timed at the speed of the interpreter.
+    hgemm_run = hg.load().hgemm_run
+    for s in sets:
+        s["ptrs"] = [(a.data_ptr(), b.data_ptr(), c.data_ptr()) for (a, b, c) in s["bufs"]]
+        s["handle"] = s["plan"]._h
+
+    def calls(s, count, sh=sh):
+        ptrs, h = s["ptrs"], s["handle"]
+        k0, n = s["next"], len(s["ptrs"])
+        for k in range(k0, k0 + count):
+            a, b, c = ptrs[k % n]
+            if hgemm_run(h, a, b, c, sh):
+                raise RuntimeError("hgemm_run failed")
         s["next"] = k0 + count
 
     for s in sets:
         calls(s, warmup)
     torch.cuda.synchronize()
 
-    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in batch_sizes] for _ in sets]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for si, s in enumerate(sets):
-        for bi, count in enumerate(batch_sizes):
-            events[si][bi][0].record(stream)
-            calls(s, count)
-            events[si][bi][1].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    def timed_region(launch_batch):
+        """All shapes, shape-major, five batches each; consecutive batches share the event between them (six
+        records per shape, not ten: a record costs about as much as one of the small kernels).  Returns
+        (per shape, per batch (start, end) events, wall seconds)."""
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(batch_sizes) + 1)] for _ in sets]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for si, s in enumerate(sets):
+            marks[si][0].record(stream)
+            for bi, count in enumerate(batch_sizes):
+                launch_batch(si, s, bi, count)
+                marks[si][bi + 1].record(stream)
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t0
+        return [[(m[bi], m[bi + 1]) for bi in range(len(batch_sizes))] for m in marks], wall_s
+
+    if not args.graph:
+        # the paper's offline mode as it stands: every call enqueued from the host, back to back
+        events, wall = timed_region(lambda si, s, bi, count: calls(s, count))
+    else:
+        # each batch captured once in a HIP graph (hgemm_run only launches kernels on the stream it is
+        # given) and replayed between the batch's events: no host enqueue cost at all, but a graph launch
+        # costs several microseconds itself, so this pays only with long batches (--steps of 200 and more)
+        graphs = []
+        for s in sets:
+            per_batch = []
+            for count in batch_sizes:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    calls(s, count, torch.cuda.current_stream().cuda_stream)
+                per_batch.append(g)
+            graphs.append(per_batch)
+        torch.cuda.synchronize()
+        events, wall = timed_region(lambda si, s, bi, count: graphs[si][bi].replay())
 
     ridge = PEAK_FP16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     per_shape = []
@@ -303,7 +339,9 @@ def metric_run(args):
         per_shape.append({
             "workload": s["cfg"] + (" cold" if s["cold"] else ""), "shape": [M, N, K], "spec": s["desc"],
             "workgroups": s["info"]["workgroups"],
-            "mean_us": mean_ms * 1e3, "median_us": float(np.median(per_call)) * 1e3, "min_us": float(per_call.min()) * 1e3,
+            "mean_us": mean_ms * 1e3,
+            "median_us": float(np.median(per_call)) * 1e3 if n_batches >= 5 else None,
+            "min_us": float(per_call.min()) * 1e3 if n_batches >= 5 else None,
             "tflops": flop / mean_ms * 1e-9, "gbs": byts / mean_ms * 1e-6,
             "frac_mfma_peak": flop / mean_ms * 1e-9 / PEAK_FP16_TFLOPS,
             "frac_hbm_peak": byts / mean_ms * 1e-6 / PEAK_HBM_GBS,
@@ -351,7 +389,7 @@ def metric_run(args):
     if args.table:
         for p in per_shape:
             print("{:8s} {:>18s}  {:9.1f} us (median {:9.1f}, min {:9.1f})  {:8.1f} TFLOP/s ({:4.1f}% MFMA)  {:8.1f} GB/s ({:4.1f}% HBM)  {}".format(
-                p["workload"], "x".join(map(str, p["shape"])), p["mean_us"], p["median_us"], p["min_us"], p["tflops"],
+                p["workload"], "x".join(map(str, p["shape"])), p["mean_us"], p["median_us"] or float("nan"), p["min_us"] or float("nan"), p["tflops"],
                 100 * p["frac_mfma_peak"], p["gbs"], 100 * p["frac_hbm_peak"], p["spec"]), file=sys.stderr)
 
     out = {
@@ -371,7 +409,8 @@ def metric_run(args):
             "workload": "C4: 200-shape grid sampled with seed 1 from {64..12288}^3, uniform[-1,1] (the value); timed in the "
                         "same steps: C2 square sweep and C5 16384^2 x {8192,16384} warm, C3 LLM skinny shapes from HBM (cold)",
             "layout": "NN row-major", "cache": "warm (C3: cold, rotating operand sets > 768 MiB)",
-            "timing": f"{steps} back-to-back calls per shape in {n_batches} batches, one event pair per batch on the launch stream",
+            "timing": (f"{steps} back-to-back calls per shape in {n_batches} batches, an event on the launch stream between batches; " +
+                       ("each batch captured once in a HIP graph and replayed" if args.graph else "calls enqueued one by one from the host")),
             "aggregate_tflops": sum(2.0 * r["shape"][0] * r["shape"][1] * r["shape"][2] for r in per_shape) * steps / wall * 1e-12,
         },
         "workloads": workloads,
@@ -397,8 +436,7 @@ def main():
         paper_grid(args)
         return
     if args.workload == "ALL":
-        if args.cold or args.server or args.graph or args.per_call_events or args.spec or args.layout != "nn" or \
-                args.library_context or args.calibrate:
+        if args.cold or args.server or args.per_call_events or args.spec or args.layout != "nn" or args.library_context or args.calibrate:
             print("bench.py: these options need a single workload (--workload C1..C5)", file=sys.stderr)
             sys.exit(2)
         metric_run(args)
