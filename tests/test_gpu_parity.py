@@ -210,6 +210,45 @@ def test_persistent_mode_every_capable_spec_bit_exact():
         assert np.array_equal(p1.view(np.uint16), p2.view(np.uint16)) and np.array_equal(p1.view(np.uint16), plain.view(np.uint16)), desc
 
 
+def test_server_mode_idle_gaps_between_calls():
+    """Server mode (Section 2.4.2): the device idles for a random 0-2 ms before every call, caches and clocks cool
+    down in between.  Every call of a plan, whatever its kind (single kernel, two-launch split-K, fused split-K
+    with its self-resetting counters, stream-K, persistent, skinny), must still give the oracle's result."""
+    import random
+    import time
+
+    rnd = random.Random(7)
+    shape = (200, 2056, 1288)
+    name, a, b = wl.exact_family_for(shape, seed=51)
+    ref = orc.hgemm(a, b)
+    da, db = to_dev(a), to_dev(b)
+    sh = torch.cuda.current_stream().cuda_stream
+    specs = [None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=3,sk=3,gm=8", "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=3,sk=5,gm=8,fr=1",
+             "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=1,sk=1,gm=8,sm=1", "mfma,bm=32,bn=64,bk=64,wm=1,wn=2,st=4,pf=3,sk=1,gm=8,ps=1"]
+    for spec in specs:
+        with hg.Plan(*shape, None, spec) as p:
+            for call in range(5):
+                torch.cuda.synchronize()
+                time.sleep(rnd.uniform(0.0, 2e-3))
+                c = torch.full((shape[0], shape[1]), float("nan"), dtype=torch.float16, device="cuda")
+                p.run(da.data_ptr(), db.data_ptr(), c.data_ptr(), sh)
+                torch.cuda.synchronize()
+                assert_bit_exact(to_host(c), ref, f"{p.describe()} call {call}")
+    shape = (16, 2056, 1288)
+    name, a, b = wl.exact_family_for(shape, seed=52)
+    ref = orc.hgemm(a, b)
+    da, db = to_dev(a), to_dev(b)
+    for spec in ("skinny,sk=4", "skinny,sk=4,fr=1"):
+        with hg.Plan(*shape, None, spec) as p:
+            for call in range(5):
+                torch.cuda.synchronize()
+                time.sleep(rnd.uniform(0.0, 2e-3))
+                c = torch.full((shape[0], shape[1]), float("nan"), dtype=torch.float16, device="cuda")
+                p.run(da.data_ptr(), db.data_ptr(), c.data_ptr(), sh)
+                torch.cuda.synchronize()
+                assert_bit_exact(to_host(c), ref, f"{p.describe()} call {call}")
+
+
 def skinny_specs(M, N, K):
     out = [c for c in hg.candidates(M, N, K) if c.startswith("skinny")]
     assert out
