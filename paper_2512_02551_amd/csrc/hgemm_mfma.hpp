@@ -90,6 +90,62 @@ __device__ inline unsigned long long load_agent(const unsigned long long* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The summing half of the fused split-K reduction: the workgroup that arrived last at a tile adds the
+// tile's S fp32 planes in split order, rounds once and stores fp16.  A lane owns groups of 4 columns
+// (QPR groups per tile row).  The loads are device-coherent and each costs a trip to memory, so a lane
+// keeps the loads of 4 column groups x 4 splits in flight at once instead of walking its groups one
+// after another; positions and splits out of range are loaded from a valid address and not added, so no
+// load sits behind a branch.
+template <int THREADS, int QPR>
+__device__ __forceinline__ void sum_split_planes(const GemmArgs& g, int m0, int n0, int rows, int t)
+{
+    constexpr int QU = 4, SU = 4;
+    const size_t plane2 = (size_t)g.M * g.N / 2;              // plane size in 8-byte words
+    const int items = rows * QPR;
+    for (int qb = 0; qb < items; qb += QU * THREADS) {
+        const unsigned long long* src[QU];
+        _Float16* dst[QU];
+        bool ok[QU];
+        float4v sum[QU];
+#pragma unroll
+        for (int j = 0; j < QU; ++j) {
+            const int q = qb + j * THREADS + t;
+            const int m = m0 + q / QPR, n = n0 + (q % QPR) * 4;
+            ok[j] = q < items && n < g.N;
+            src[j] = (const unsigned long long*)(g.partial + (ok[j] ? (size_t)m * g.N + n : (size_t)m0 * g.N + n0));
+            dst[j] = g.C + (size_t)m * g.ldc + n;
+            sum[j] = float4v{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int s0 = 0; s0 < g.splits; s0 += SU) {
+            union { float4v f; unsigned long long u[2]; } v[SU][QU];
+#pragma unroll
+            for (int u = 0; u < SU; ++u) {
+                const size_t off = (size_t)min(s0 + u, g.splits - 1) * plane2;
+#pragma unroll
+                for (int j = 0; j < QU; ++j) {
+                    v[u][j].u[0] = load_agent(src[j] + off);
+                    v[u][j].u[1] = load_agent(src[j] + off + 1);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < SU; ++u) {
+                if (s0 + u < g.splits) {
+#pragma unroll
+                    for (int j = 0; j < QU; ++j) sum[j] += v[u][j].f;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < QU; ++j) {
+            if (!ok[j]) continue;
+            half4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[j][e];
+            *(half4*)dst[j] = o;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Tile order.  Hardware deals workgroup ids round-robin to the 8 XCDs, each
 // with a private L2.  Step 1 renumbers ids so that, inside every run of 256
@@ -648,33 +704,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
             __syncthreads();
             if (*flag != g.splits - 1) return;
-            const int rows = min(C::BM, g.M - m0);
-            const size_t plane = (size_t)g.M * g.N;
-            constexpr int QPR = C::BN / 4;                      // groups of 4 columns per tile row
-            for (int q = threadIdx.x; q < rows * QPR; q += C::THREADS) {
-                const int m = m0 + q / QPR, n = n0 + (q % QPR) * 4;
-                if (n >= g.N) continue;
-                const unsigned long long* src = (const unsigned long long*)(g.partial + (size_t)m * g.N + n);
-                float4v sum = {0.f, 0.f, 0.f, 0.f};
-                for (int s0 = 0; s0 < g.splits; s0 += 8) {
-                    union { float4v f; unsigned long long u[2]; } v[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        v[u].u[0] = v[u].u[1] = 0ull;
-                        if (s0 + u < g.splits) {
-                            v[u].u[0] = load_agent(src + (size_t)(s0 + u) * (plane / 2));
-                            v[u].u[1] = load_agent(src + (size_t)(s0 + u) * (plane / 2) + 1);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (s0 + u < g.splits) sum += v[u].f;
-                }
-                half4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
-                *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
-            }
+            sum_split_planes<C::THREADS, C::BN / 4>(g, m0, n0, min(C::BM, g.M - m0), (int)threadIdx.x);
         }
     }
     if (PERSIST && !has_next) wait_vmcnt<0>();        // the final tile's out-of-range copies

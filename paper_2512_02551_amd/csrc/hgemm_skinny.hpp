@@ -185,32 +185,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(GemmArgs g)
     }
     __syncthreads();
     if (*flag != g.splits - 1) return;
-    const size_t plane = (size_t)g.M * g.N;
-    constexpr int QPR = kSkinnyCols / 4;
-    for (int q = t; q < g.M * QPR; q += 256) {
-        const int m = q / QPR, n = n0 + (q % QPR) * 4;
-        if (n >= g.N) continue;
-        const unsigned long long* src = (const unsigned long long*)(g.partial + (size_t)m * g.N + n);
-        float4v sum = {0.f, 0.f, 0.f, 0.f};
-        for (int s0 = 0; s0 < g.splits; s0 += 8) {
-            union { float4v f; unsigned long long u[2]; } v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                v[u].u[0] = v[u].u[1] = 0ull;
-                if (s0 + u < g.splits) {
-                    v[u].u[0] = load_agent(src + (size_t)(s0 + u) * (plane / 2));
-                    v[u].u[1] = load_agent(src + (size_t)(s0 + u) * (plane / 2) + 1);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < g.splits) sum += v[u].f;
-        }
-        half4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (_Float16)sum[e];
-        *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
-    }
+    sum_split_planes<256, kSkinnyCols / 4>(g, 0, n0, g.M, t);
 }
 
 }  // namespace hgemm

@@ -24,6 +24,7 @@ import argparse
 import json
 import os
 import random
+import re
 import sys
 import time
 
@@ -105,6 +106,9 @@ def main():
                     help="comma-separated tuning logs: instead of every candidate, time only the specs these logs record "
                          "for the shape (winners and runners-up) -- a refinement pass that settles close calls between "
                          "earlier sweeps with many more rounds per candidate")
+    ap.add_argument("--fused-twins", action="store_true",
+                    help="with --candidates-from: also time, for every recorded split-K spec, its twin with the reduction "
+                         "fused into the kernel (fr=1), and tune only the shapes that have a split-K spec on record")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
     ap.add_argument("--cold-workloads", default="C3",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
@@ -158,8 +162,19 @@ def main():
                         sp = sp.replace(",pad=1", "")
                         if sp and sp not in specs:
                             specs.append(sp)
+    if args.fused_twins:
+        def splits(sp):
+            m = re.search(r"sk=(\d+)", sp)
+            return int(m.group(1)) if m else 1
+        recorded = {k: v for k, v in recorded.items() if any(splits(sp) > 1 for sp in v)}
+        for specs in recorded.values():
+            for sp in list(specs):
+                if splits(sp) > 1 and "fr=1" not in sp and "sm=1" not in sp and sp + ",fr=1" not in specs:
+                    specs.append(sp + ",fr=1")
+        shapes = [s for s in shapes if s in recorded]
 
     rot = {"sets": None, "i": 0, "graph": False, "graphs": {}}
+    hgemm_run = hg.load().hgemm_run          # bound once: the eager batches should cost the host as little as Python allows
 
     def timed(plan, a, b, c, rounds):
         """One sample: `rounds` back-to-back calls between one pair of events, per-call time.  With
@@ -183,12 +198,16 @@ def main():
             e1.record(stream)
             torch.cuda.synchronize()
             return [e0.elapsed_time(e1) / rounds]
+        h = plan._h
+        if rot["sets"] is not None:
+            ptrs = [rot["ptrs"][(rot["i"] + r) % len(rot["ptrs"])] for r in range(rounds)]
+            rot["i"] += rounds
+        else:
+            ptrs = [(a.data_ptr(), b.data_ptr(), c.data_ptr())] * rounds
         e0.record(stream)
-        for r in range(rounds):
-            if rot["sets"] is not None:
-                a, b, c = rot["sets"][rot["i"] % len(rot["sets"])]
-                rot["i"] += 1
-            plan.run(a.data_ptr(), b.data_ptr(), c.data_ptr(), sh)
+        for (pa, pb, pc) in ptrs:
+            if hgemm_run(h, pa, pb, pc, sh):
+                raise RuntimeError("hgemm_run failed")
         e1.record(stream)
         torch.cuda.synchronize()
         return [e0.elapsed_time(e1) / rounds]
@@ -208,6 +227,7 @@ def main():
             per_set = 2 * (M * K + K * N + M * N)
             n_sets = max(2, min(64, -(-768 * 2 ** 20 // per_set)))
             rot["sets"] = [(a, b, c)] + [(a.clone(), b.clone(), torch.empty_like(c)) for _ in range(n_sets - 1)]
+            rot["ptrs"] = [(x.data_ptr(), y.data_ptr(), z.data_ptr()) for (x, y, z) in rot["sets"]]
         rot["graph"] = rot["sets"] is None and 2.0 * M * N * K < args.graph_below_flop
         rot["graphs"] = {}
         # The gate: the generic kernel's result on the integer inputs.  Above 2^37 multiply-adds the
