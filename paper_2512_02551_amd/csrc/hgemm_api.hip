@@ -564,9 +564,10 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     a.lda = (int)p->lay.lda; a.ldb = s.tb ? (int)K : (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
     a.tiles_m = (int)((M + e->bm - 1) / e->bm);
     a.tiles_n = (int)((N + e->bn - 1) / e->bn);
-    if ((int64_t)a.tiles_m * a.tiles_n >= ((int64_t)1 << 31)) return HGEMM_ERR_UNSUPPORTED;
+    if ((int64_t)a.tiles_m * a.tiles_n >= ((int64_t)1 << 24)) return HGEMM_ERR_UNSUPPORTED;      // tile_coords()
     // with a handful of tiles the order cannot matter: spare the kernel the arithmetic of the map
     a.swizzle = (int64_t)a.tiles_m * a.tiles_n <= 16 ? 0 : s.gm;
+    set_tile_map(a);
     // split K into ranges that are multiples of BK; drop splits that would be empty
     int64_t ktiles = (K + e->bk - 1) / e->bk;
     const int64_t sk = effective_splits(ktiles, s.sk);
@@ -1076,10 +1077,17 @@ int64_t hgemm_tile_of_workgroup(int64_t wg, int64_t tiles_m, int64_t tiles_n, in
 {
     if (tiles_m <= 0 || tiles_n <= 0 || wg < 0 || wg >= tiles_m * tiles_n || swizzle < 0) return -1;
     const int64_t tile = tile_of_workgroup(wg, tiles_m, tiles_n, swizzle);
-    // the kernels use the 32-bit form of the same map: report a disagreement instead of hiding it
-    if (tiles_m * tiles_n < ((int64_t)1 << 31) && swizzle < ((int64_t)1 << 31) &&
-        tile_of_workgroup32((int)wg, (int)tiles_m, (int)tiles_n, (int)swizzle) != tile)
-        return -2;
+    // the kernels use the multiplication form of the same map: report a disagreement instead of hiding it
+    if (tiles_m * tiles_n < ((int64_t)1 << 24)) {
+        GemmArgs a{};
+        a.tiles_m = (int)tiles_m;
+        a.tiles_n = (int)tiles_n;
+        a.swizzle = (int)std::min<int64_t>(swizzle, tiles_m);
+        set_tile_map(a);
+        unsigned tm = 0, tn = 0;
+        tile_coords((unsigned)wg, a, tm, tn);
+        if ((int64_t)tm * tiles_n + tn != tile) return -2;
+    }
     return tile;
 }
 

@@ -50,6 +50,25 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 #define HGEMM_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
+// Division of a tile id by a launch constant without a divide instruction sequence: for 0 <= n < 2^24 and
+// d >= 1, floor(n / d) = (((n << 8) * m) >> 32) >> l with l = ceil(log2 d) and m = ceil(2^(24 + l) / d) <= 2^25
+// (m * d = 2^(24 + l) + r with 0 <= r < d <= 2^l, so n * m / 2^(24 + l) exceeds n / d by less than 1 / d).
+struct FastDiv {
+    unsigned m, l;
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f{0, 0};
+    if (d == 0) d = 1;
+    while ((1ull << f.l) < d) ++f.l;
+    f.m = (unsigned)((((unsigned long long)1 << (24 + f.l)) + d - 1) / d);
+    return f;
+}
+__host__ __device__ inline unsigned fast_div(unsigned n, FastDiv f)
+{
+    return (unsigned)(((unsigned long long)(n << 8) * f.m) >> 32) >> f.l;
+}
+
 struct GemmArgs {
     const _Float16* A;
     const _Float16* B;
@@ -60,6 +79,9 @@ struct GemmArgs {
     int lda, ldb, ldc;   // elements
     int tiles_m, tiles_n;
     int swizzle;         // group height in tiles for the tile order; 0 = row-major
+    // divisors of the tile order, fixed per launch (set_tile_map): tiles_n; one band = group * tiles_n
+    // tiles; the rows of a full band; the rows of the last, shorter band
+    FastDiv by_tiles_n, by_band, by_rows, by_last_rows;
     int k_per_split;     // K range of one split, a multiple of BK (== K rounded up when not split)
     int splits;
     // stream-K: the first dp_tiles tiles (in tile order) get one workgroup each; the K-tile
@@ -180,32 +202,41 @@ __host__ __device__ inline int64_t tile_of_workgroup(int64_t wg, int64_t tiles_m
     return logical;
 }
 
-// The same map in 32-bit arithmetic for the kernels (a 64-bit division costs a few hundred cycles on
-// the GPU, and a 3 us kernel does several of them): valid while tiles_m * tiles_n < 2^31, which the
-// host checks.
-__host__ __device__ inline int tile_of_workgroup32(int wg, int tiles_m, int tiles_n, int group)
+// What the kernels use: the same map in 32-bit arithmetic, straight to tile coordinates, with every
+// division by a launch constant replaced by a multiplication (a 3 us kernel otherwise spends a tenth of
+// its time on integer divisions before its first load).  Valid while tiles_m * tiles_n < 2^24, which
+// the host checks; the host can also compare it with the form above.
+inline void set_tile_map(GemmArgs& g)
 {
-    if (group <= 0) return wg;
-    const unsigned total = (unsigned)tiles_m * (unsigned)tiles_n;
-    const unsigned XCDS = 8, WAVE = 256;
-    const unsigned uwg = (unsigned)wg;
-    const unsigned base = uwg & ~(WAVE - 1);
-    const unsigned span = (total - base < WAVE) ? (total - base) : WAVE;
-    const unsigned within = uwg - base;
-    const unsigned xcd = within % XCDS, seq = within / XCDS;
-    const unsigned q = span / XCDS, r = span % XCDS;
-    const unsigned start = xcd * q + (xcd < r ? xcd : r);
-    const unsigned logical = base + start + seq;
-    // a group taller than the grid is the whole grid (and keeps group * tiles_n inside 32 bits)
-    const unsigned ugroup = (unsigned)(group < tiles_m ? group : tiles_m), utn = (unsigned)tiles_n;
-    const unsigned band_sz = ugroup * utn;
-    const unsigned band = logical / band_sz;
-    const unsigned first_m = band * ugroup;
-    const unsigned rows = ((unsigned)tiles_m - first_m < ugroup) ? ((unsigned)tiles_m - first_m) : ugroup;
-    const unsigned in_band = logical - band * band_sz;
-    const unsigned tm = first_m + in_band % rows;
-    const unsigned tn = in_band / rows;
-    return (int)(tm * utn + tn);
+    const unsigned group = (unsigned)(g.swizzle < g.tiles_m ? g.swizzle : g.tiles_m);
+    g.by_tiles_n = make_fastdiv((unsigned)g.tiles_n);
+    g.by_band = make_fastdiv(group * (unsigned)g.tiles_n);
+    g.by_rows = make_fastdiv(group);
+    g.by_last_rows = make_fastdiv(group ? (unsigned)g.tiles_m % group : 1u);
+}
+__host__ __device__ inline void tile_coords(unsigned wg, const GemmArgs& g, unsigned& tm, unsigned& tn)
+{
+    const unsigned utn = (unsigned)g.tiles_n;
+    if (g.swizzle <= 0) {
+        tm = fast_div(wg, g.by_tiles_n);
+        tn = wg - tm * utn;
+        return;
+    }
+    const unsigned total = (unsigned)g.tiles_m * utn;
+    const unsigned base = wg & ~255u;
+    const unsigned span = (total - base < 256u) ? (total - base) : 256u;
+    const unsigned within = wg - base;
+    const unsigned xcd = within & 7u, seq = within >> 3;
+    const unsigned q = span >> 3, r = span & 7u;
+    const unsigned logical = base + xcd * q + (xcd < r ? xcd : r) + seq;
+    const unsigned group = (unsigned)(g.swizzle < g.tiles_m ? g.swizzle : g.tiles_m);
+    const unsigned band = fast_div(logical, g.by_band);
+    const unsigned first_m = band * group;
+    const bool last = (unsigned)g.tiles_m - first_m < group;
+    const unsigned rows = last ? (unsigned)g.tiles_m - first_m : group;
+    const unsigned in_band = logical - band * group * utn;
+    tn = fast_div(in_band, last ? g.by_last_rows : g.by_rows);
+    tm = first_m + in_band - tn * rows;
 }
 
 // PF = register prefetch distance in k-steps (Sections 5.3.1 and 5.3.2: PF = 1 is the
@@ -314,6 +345,14 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     constexpr bool PERSIST = MODE == MODE_PERSIST;
     static_assert(!PERSIST || C::CAN_PERSIST, "epilogue staging must fit in one stage");
 
+    // All arguments the set-up reads are pulled into scalar registers here, in one batch of loads:
+    // left to itself the compiler fetches some of them later, inside branches, and every such fetch is
+    // another round trip to memory in front of the first copy (short kernels are latency chains).
+    asm volatile("" :: "s"(g.A), "s"(g.B), "s"(g.C), "s"(g.M), "s"(g.N), "s"(g.K), "s"(g.lda), "s"(g.ldb), "s"(g.ldc),
+                 "s"(g.tiles_m), "s"(g.tiles_n), "s"(g.swizzle), "s"(g.k_per_split), "s"(g.splits));
+    asm volatile("" :: "s"(g.by_tiles_n.m), "s"(g.by_tiles_n.l), "s"(g.by_band.m), "s"(g.by_band.l), "s"(g.by_rows.m),
+                 "s"(g.by_rows.l), "s"(g.by_last_rows.m), "s"(g.by_last_rows.l));
+
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
@@ -360,10 +399,10 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     int m0, n0;        // the tile being multiplied and stored
     int lm0, ln0;      // the tile the copies read (the same one, except in persistent mode near the end of a tile)
     auto tile_origin = [&](int id, int& tm0, int& tn0) {
-        const unsigned tile = (unsigned)tile_of_workgroup32(id, g.tiles_m, g.tiles_n, g.swizzle);
-        const unsigned tm = tile / (unsigned)g.tiles_n;
+        unsigned tm, tn;
+        tile_coords((unsigned)id, g, tm, tn);
         tm0 = (int)tm * C::BM;
-        tn0 = (int)(tile - tm * (unsigned)g.tiles_n) * C::BN;
+        tn0 = (int)tn * C::BN;
     };
     tile_origin(tile_id, m0, n0);
     const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
@@ -749,9 +788,10 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmArgs g)
         const int wb = w_first * ipw, we = min(wb + ipw, g.sk_total_iters);
         if (wb <= it0 && we >= it1) return;
     }
-    const int tile = tile_of_workgroup32(g.dp_tiles + t, g.tiles_m, g.tiles_n, g.swizzle);
-    const int m0 = (tile / g.tiles_n) * BM;
-    const int n0 = (tile % g.tiles_n) * BN;
+    unsigned tm, tn;
+    tile_coords((unsigned)(g.dp_tiles + t), g, tm, tn);
+    const int m0 = (int)tm * BM;
+    const int n0 = (int)tn * BN;
     // blockIdx.y picks a slice of 1024 groups of 4 consecutive columns
     for (int q = blockIdx.y * 1024 + threadIdx.x; q < min((int)(blockIdx.y + 1) * 1024, BM * BN / 4); q += 256) {
         const int r = q / (BN / 4), c = (q % (BN / 4)) * 4;
