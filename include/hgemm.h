@@ -107,6 +107,30 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
                          void* hip_stream);
 
 /*
+ * hgemm_run_many -- enqueue `count` calls of one plan back to back on
+ * `hip_stream` (Section 2.4.2's offline mode: the same kernel executed
+ * consecutively, without pauses).  Call i works on operand set j = (first + i)
+ * % sets, C[j] = A[j] * B[j]; the result is that of `count` calls of hgemm_run
+ * in a loop.  The
+ * loop runs inside the library so that a caller in an interpreted language
+ * pays its per-call overhead once per batch: kernels of 2-3 us are otherwise
+ * enqueued more slowly than the GPU executes them.
+ *   count       number of calls, >= 0
+ *   sets        number of operand sets, >= 1
+ *   first       set of the first call, 0 <= first < sets (a caller that cycles
+ *               through sets larger than the caches continues where its last
+ *               batch stopped)
+ *   A, B, C     HOST arrays of `sets` DEVICE pointers each (read during the
+ *               call only); the operands they point to are as in hgemm_run
+ *   hip_stream  as hgemm_run
+ * Errors: as hgemm_run; stops at the first call that fails (calls already
+ * enqueued stay enqueued).
+ */
+hgemm_status_t hgemm_run_many(hgemm_plan_t plan, int64_t count, int64_t sets, int64_t first,
+                              const void* const* A, const void* const* B, void* const* C,
+                              void* hip_stream);
+
+/*
  * hgemm_run_static -- plan and enqueue C = A*B in one call that allocates
  * nothing, for callers that cannot allocate: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same operation,

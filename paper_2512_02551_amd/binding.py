@@ -17,7 +17,7 @@ EXPORTS = (
     "hgemm_plan", "hgemm_plan_override", "hgemm_run", "hgemm_destroy", "hgemm_status_string",
     "hgemm_plan_describe", "hgemm_plan_workspace_bytes", "hgemm_plan_launch_info", "hgemm_spec_help",
     "hgemm_candidates", "hgemm_tiles", "hgemm_padded", "hgemm_tile_of_workgroup",
-    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us", "hgemm_run_static",
+    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us", "hgemm_run_static", "hgemm_run_many",
 )
 
 STATIC_SCRATCH_BYTES = 64 << 20      # HGEMM_STATIC_SCRATCH_BYTES of include/hgemm.h
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.hgemm_plan_override.argtypes = [ctypes.POINTER(vp), i64, i64, i64, lp, cp]
     lib.hgemm_run.restype = ci
     lib.hgemm_run.argtypes = [vp, vp, vp, vp, vp]
+    lib.hgemm_run_many.restype = ci
+    lib.hgemm_run_many.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     lib.hgemm_run_static.restype = ci
     lib.hgemm_run_static.argtypes = [i64, i64, i64, lp, vp, vp, vp, vp]
     lib.hgemm_destroy.restype = ci
@@ -175,6 +177,20 @@ class Plan:
         st = load().hgemm_run(self._h, a_ptr, b_ptr, c_ptr, stream)
         if st != 0:
             raise HgemmError(st, "hgemm_run")
+
+    def pointer_sets(self, sets):
+        """Marshal [(a_ptr, b_ptr, c_ptr), ...] into the three host arrays hgemm_run_many takes."""
+        n = len(sets)
+        arr = ctypes.c_void_p * n
+        return (n, arr(*[s[0] for s in sets]), arr(*[s[1] for s in sets]), arr(*[s[2] for s in sets]))
+
+    def run_many(self, count: int, sets, stream: int = 0, first: int = 0) -> None:
+        """hgemm_run_many: `count` back-to-back calls, call i on operand set (first + i) % len(sets).
+        `sets` is a list of (a_ptr, b_ptr, c_ptr) or the result of pointer_sets()."""
+        n, a, b, c = sets if isinstance(sets[0], int) else self.pointer_sets(sets)
+        st = load().hgemm_run_many(self._h, count, n, first, a, b, c, stream)
+        if st != 0:
+            raise HgemmError(st, "hgemm_run_many")
 
     def run_status(self, a_ptr, b_ptr, c_ptr, stream: int = 0) -> int:
         return int(load().hgemm_run(self._h, a_ptr, b_ptr, c_ptr, stream))

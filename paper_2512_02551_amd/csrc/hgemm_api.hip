@@ -877,6 +877,19 @@ hgemm_status_t hgemm_run(hgemm_plan_t plan, const void* A, const void* B, void* 
     return run_plan(plan, A, B, C, hip_stream);
 }
 
+hgemm_status_t hgemm_run_many(hgemm_plan_t plan, int64_t count, int64_t sets, int64_t first, const void* const* A,
+                              const void* const* B, void* const* C, void* hip_stream)
+{
+    if (!plan || count < 0 || sets < 1 || first < 0 || first >= sets || !A || !B || !C) return HGEMM_ERR_INVALID_ARG;
+    int64_t set = first;
+    for (int64_t i = 0; i < count; ++i) {
+        const hgemm_status_t st = run_plan(plan, A[set], B[set], C[set], hip_stream);
+        if (st != HGEMM_OK) return st;
+        if (++set == sets) set = 0;
+    }
+    return HGEMM_OK;
+}
+
 hgemm_status_t hgemm_run_static(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, const void* A, const void* B,
                                 void* C, void* hip_stream)
 {

@@ -249,6 +249,32 @@ def test_server_mode_idle_gaps_between_calls():
                 assert_bit_exact(to_host(c), ref, f"{p.describe()} call {call}")
 
 
+def test_run_many_equals_a_loop_of_runs_and_rotates_operand_sets():
+    """hgemm_run_many (Section 2.4.2's offline mode, the loop inside the library): call i works on operand set
+    (first + i) % sets; every set's result must be the oracle's, for single-kernel, two-launch and fused plans,
+    and sets that no call reaches stay untouched."""
+    shape = (72, 520, 1096)
+    sets = []
+    for seed in (61, 62, 63, 64):
+        name, a, b = wl.exact_family_for(shape, seed=seed)
+        sets.append((to_dev(a), to_dev(b), orc.hgemm(a, b)))
+    sh = torch.cuda.current_stream().cuda_stream
+    for spec in (None, "mfma,bm=32,bn=64,bk=64,wm=1,wn=2,st=4,pf=3,sk=4,gm=8", "mfma,bm=32,bn=64,bk=64,wm=1,wn=2,st=4,pf=3,sk=4,gm=8,fr=1"):
+        with hg.Plan(*shape, None, spec) as p:
+            for count, first in ((4, 0), (9, 2), (2, 3), (0, 1)):
+                cs = [torch.full((shape[0], shape[1]), float("nan"), dtype=torch.float16, device="cuda") for _ in sets]
+                p.run_many(count, [(a.data_ptr(), b.data_ptr(), c.data_ptr()) for (a, b, _), c in zip(sets, cs)], sh, first)
+                torch.cuda.synchronize()
+                reached = {(first + i) % len(sets) for i in range(count)}
+                for j, ((_, _, ref), c) in enumerate(zip(sets, cs)):
+                    if j in reached:
+                        assert_bit_exact(to_host(c), ref, f"{p.describe()} count {count} first {first} set {j}")
+                    else:
+                        assert bool(torch.isnan(c).all()), f"set {j} was written although no call reaches it"
+            with pytest.raises(hg.HgemmError):
+                p.run_many(1, [(sets[0][0].data_ptr(), sets[0][1].data_ptr(), 0)], sh, 1)      # first >= sets
+
+
 def skinny_specs(M, N, K):
     out = [c for c in hg.candidates(M, N, K) if c.startswith("skinny")]
     assert out

@@ -33,6 +33,13 @@ def test_status_strings(lib):
     assert "gfx950" in hg.status_string(5)
 
 
+def test_run_entry_points_refuse_a_null_plan_before_touching_the_gpu(lib):
+    import ctypes
+    one = (ctypes.c_void_p * 1)(0)
+    assert lib.hgemm_run(None, None, None, None, None) == 1
+    assert lib.hgemm_run_many(None, 1, 1, 0, one, one, one, None) == 1
+
+
 def test_padding_arithmetic_matches_the_papers_example(lib):
     # Section 5.2: M = 8192, BM = 160 -> 52 tiles, 8320 rows
     assert hg.tiles(8192, 160) == 52
