@@ -109,6 +109,11 @@ def main():
     ap.add_argument("--fused-twins", action="store_true",
                     help="with --candidates-from: also time, for every recorded split-K spec, its twin with the reduction "
                          "fused into the kernel (fr=1), and tune only the shapes that have a split-K spec on record")
+    ap.add_argument("--extra-specs", default="",
+                    help="with --candidates-from: ';'-separated specs timed on top of the recorded ones (a new "
+                         "configuration tried on the shapes where a given kind of spec is on record)")
+    ap.add_argument("--only-recorded-with", default="",
+                    help="with --candidates-from: tune only the shapes that have a spec containing this text on record")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
     ap.add_argument("--cold-workloads", default="C3",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
@@ -162,6 +167,11 @@ def main():
                         sp = sp.replace(",pad=1", "")
                         if sp and sp not in specs:
                             specs.append(sp)
+    if args.only_recorded_with:
+        recorded = {k: v for k, v in recorded.items() if any(args.only_recorded_with in sp for sp in v)}
+        shapes = [s for s in shapes if s in recorded]
+    for specs in recorded.values():
+        specs += [sp for sp in args.extra_specs.split(";") if sp and sp not in specs]
     if args.fused_twins:
         def splits(sp):
             m = re.search(r"sk=(\d+)", sp)
