@@ -99,6 +99,7 @@ def main():
     ap.add_argument("--max-shapes", type=int, default=0)
     ap.add_argument("--max-k", type=int, default=0, help="only shapes with K <= this (re-tuning a slice of a workload)")
     ap.add_argument("--max-flop", type=float, default=0.0, help="only shapes with 2*M*N*K <= this")
+    ap.add_argument("--min-flop", type=float, default=0.0, help="only shapes with 2*M*N*K >= this")
     ap.add_argument("--graph-below-flop", type=float, default=2e10,
                     help="shapes with 2*M*N*K below this are timed as replays of a captured graph of the batch: their "
                          "kernels are shorter than the host's enqueue time, which would otherwise hide every difference")
@@ -152,6 +153,8 @@ def main():
         shapes = [s for s in shapes if s[2] <= args.max_k]
     if args.max_flop:
         shapes = [s for s in shapes if 2.0 * s[0] * s[1] * s[2] <= args.max_flop]
+    if args.min_flop:
+        shapes = [s for s in shapes if 2.0 * s[0] * s[1] * s[2] >= args.min_flop]
     if args.max_shapes:
         shapes = shapes[:args.max_shapes]
     rng = random.Random(0)
