@@ -48,6 +48,10 @@ def _load():
             lib.oracle_hgemm_at.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp]
             lib.oracle_hgemm_sum_at.restype = ci
             lib.oracle_hgemm_sum_at.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp]
+            lib.oracle_hgemm_acc16.restype = ci
+            lib.oracle_hgemm_acc16.argtypes = [i64, i64, i64, i64, vp, i64, vp, i64, ci, vp, i64]
+            lib.oracle_hgemm_acc16_at.restype = ci
+            lib.oracle_hgemm_acc16_at.argtypes = [i64, i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp]
             lib.oracle_half_to_double_n.restype = None
             lib.oracle_half_to_double_n.argtypes = [i64, vp, vp]
             lib.oracle_double_to_half_n.restype = None
@@ -125,6 +129,39 @@ def hgemm_sum_at(A, B, ii, jj, b_col_major: bool = False) -> np.ndarray:
     if rc != 0:
         raise RuntimeError("oracle_hgemm_sum_at rejected its arguments")
     return out
+
+
+def hgemm_acc16(A, B, block: int = 16, b_col_major: bool = False) -> np.ndarray:
+    """The 16-bit accumulator variant (Section 1: fp16 accumulators are a valid choice; Section 2.3.2's
+    exact-match test is built for them): the running sum is an fp16 value that takes in ``block`` products at a
+    time, one round-to-nearest-even per block.  ``block`` = 16 is one matrix-core instruction."""
+    A = _as_u16(A, "A")
+    B = _as_u16(B, "B")
+    M, N, K = _shapes(A, B, b_col_major)
+    C = np.empty((M, N), dtype=np.uint16)
+    rc = _load().oracle_hgemm_acc16(M, N, K, int(block), A.ctypes.data, A.shape[1], B.ctypes.data, B.shape[1],
+                                    int(bool(b_col_major)), C.ctypes.data, N)
+    if rc != 0:
+        raise RuntimeError("oracle_hgemm_acc16 rejected its arguments")
+    return C.view(np.float16)
+
+
+def hgemm_acc16_at(A, B, ii, jj, block: int = 16, b_col_major: bool = False) -> np.ndarray:
+    """Values of the 16-bit accumulator variant at chosen positions."""
+    A = _as_u16(A, "A")
+    B = _as_u16(B, "B")
+    M, N, K = _shapes(A, B, b_col_major)
+    ii = np.ascontiguousarray(ii, dtype=np.int64)
+    jj = np.ascontiguousarray(jj, dtype=np.int64)
+    if ii.shape != jj.shape or ii.ndim != 1:
+        raise ValueError("ii and jj must be 1-D and of equal length")
+    out = np.empty(ii.shape[0], dtype=np.uint16)
+    rc = _load().oracle_hgemm_acc16_at(M, N, K, int(block), A.ctypes.data, A.shape[1], B.ctypes.data, B.shape[1],
+                                       int(bool(b_col_major)), ii.shape[0], ii.ctypes.data, jj.ctypes.data,
+                                       out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle_hgemm_acc16_at rejected its arguments (index out of range?)")
+    return out.view(np.float16)
 
 
 def half_bits_to_double(h) -> np.ndarray:

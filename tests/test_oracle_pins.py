@@ -412,3 +412,93 @@ def test_pins_catch_planted_mistakes(name):
     # and the real oracle passes both
     assert np.array_equal(orc.hgemm(Ai.astype(np.float16), Bi.astype(np.float16)).astype(np.int64), Ai @ Bi)
     assert np.array_equal(orc.hgemm(A, B).view(np.uint16), want.view(np.uint16))
+
+
+# ---------------------------------------------------------------------------
+# the 16-bit accumulator variant (Section 1: fp16 accumulators are a valid choice for fp16 inputs;
+# Section 2.3.2: the exact-match test keeps every output at or below 2048 for their sake)
+# ---------------------------------------------------------------------------
+
+def _acc16_by_hand(A, B, block):
+    """Independent emulation: exact block sums in int64 units of 2^-6 (inputs are multiples of 1/8), the running
+    value rounded to fp16 by numpy's own float64 -> float16 cast after every block."""
+    Ai = np.rint(A.astype(np.float64) * 8).astype(np.int64)
+    Bi = np.rint(B.astype(np.float64) * 8).astype(np.int64)
+    M, K = Ai.shape
+    N = Bi.shape[1]
+    acc = np.zeros((M, N), dtype=np.float16)
+    for k0 in range(0, K, block):
+        s = Ai[:, k0:k0 + block] @ Bi[k0:k0 + block, :]                       # exact
+        acc = (acc.astype(np.float64) + s.astype(np.float64) / 64.0).astype(np.float16)
+    return acc
+
+
+@pytest.mark.parametrize("block", [1, 3, 16, 32])
+@pytest.mark.parametrize("M,N,K", [(3, 4, 40), (2, 5, 16), (4, 3, 97), (1, 1, 1), (5, 2, 33)])
+def test_acc16_matches_an_independent_emulation_on_exactly_representable_inputs(M, N, K, block):
+    rng = np.random.default_rng(1000 * K + block)
+    A = (rng.integers(-32, 33, size=(M, K)) / 8.0).astype(np.float16)       # multiples of 1/8, |x| <= 4
+    B = (rng.integers(-32, 33, size=(K, N)) / 8.0).astype(np.float16)
+    want = _acc16_by_hand(A, B, block)
+    got = orc.hgemm_acc16(A, B, block)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    ii, jj = np.divmod(np.arange(M * N), N)
+    assert np.array_equal(orc.hgemm_acc16_at(A, B, ii, jj, block).view(np.uint16), want.ravel().view(np.uint16))
+    assert np.array_equal(orc.hgemm_acc16(A, np.ascontiguousarray(B.T), block, b_col_major=True).view(np.uint16), want.view(np.uint16))
+
+
+def test_acc16_paper_exact_match_property_binary_inputs_up_to_2048():
+    """Section 2.3.2: with inputs in {0, 1} every output is a count; an fp16 accumulator holds counts up to 2048
+    exactly, whatever the cadence of its roundings."""
+    rng = np.random.default_rng(5)
+    K = 4000
+    p = np.sqrt(0.45)                                                           # E[c] = 1800, max stays under 2048
+    A = (rng.random((12, K)) < p).astype(np.float16)
+    B = (rng.random((K, 9)) < p).astype(np.float16)
+    exact = A.astype(np.int64) @ B.astype(np.int64)
+    assert exact.max() <= 2048 and exact.min() > 1024
+    for block in (1, 16, 64):
+        assert np.array_equal(orc.hgemm_acc16(A, B, block).astype(np.int64), exact), block
+
+
+def test_acc16_closed_forms_tell_the_cadences_apart():
+    ones_a = np.ones((1, 70000), dtype=np.float16)
+    ones_b = np.ones((70000, 1), dtype=np.float16)
+    # one product at a time: 2048 + 1 ties to 2048 and the sum sticks there
+    assert float(orc.hgemm_acc16(ones_a, ones_b, 1)[0, 0]) == 2048.0
+    # 16 at a time: exact while multiples of 16 are representable, i.e. up to 32768; 32768 + 16 ties to 32768
+    assert float(orc.hgemm_acc16(ones_a, ones_b, 16)[0, 0]) == 32768.0
+    assert float(orc.hgemm_acc16(ones_a[:, :32768], ones_b[:32768], 16)[0, 0]) == 32768.0
+    assert float(orc.hgemm_acc16(ones_a[:, :20000], ones_b[:20000], 16)[0, 0]) == 20000.0
+    # 32 at a time: exact all the way to 65504 + 32 = 65536, which overflows to infinity
+    assert np.isposinf(orc.hgemm_acc16(ones_a, ones_b, 32)[0, 0])
+    # a ragged last block is not dropped: 40 = 16 + 16 + 8
+    assert float(orc.hgemm_acc16(ones_a[:, :40], ones_b[:40], 16)[0, 0]) == 40.0
+    # one block covering all of K is the fp64-accumulate definition
+    assert float(orc.hgemm_acc16(ones_a[:, :40000], ones_b[:40000], 1 << 20)[0, 0]) == float(orc.hgemm(ones_a[:, :40000], ones_b[:40000])[0, 0]) == 40000.0
+
+
+def test_acc16_with_k_within_one_block_is_the_definition_on_real_inputs():
+    rng = np.random.default_rng(9)
+    for K in (1, 7, 16):
+        A = rng.standard_normal((9, K)).astype(np.float16)
+        B = rng.standard_normal((K, 11)).astype(np.float16)
+        assert np.array_equal(orc.hgemm_acc16(A, B, 16).view(np.uint16), orc.hgemm(A, B).view(np.uint16))
+    A = rng.standard_normal((6, 200)).astype(np.float16)
+    B = rng.standard_normal((200, 5)).astype(np.float16)
+    assert np.array_equal(orc.hgemm_acc16(A, B, 200).view(np.uint16), orc.hgemm(A, B).view(np.uint16))
+    # and with many blocks the error against the definition stays what fp16 accumulation allows (a few ulp of the
+    # running sum per block), far inside the parity tolerance
+    got = orc.hgemm_acc16(A, B, 16).astype(np.float64)
+    ref = orc.hgemm(A, B).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 1e-2 * np.maximum(1.0, np.abs(ref)))
+    assert not np.array_equal(got, ref)
+
+
+def test_acc16_rejects_bad_arguments_and_handles_empty_shapes():
+    a = np.ones((2, 3), dtype=np.float16)
+    b = np.ones((3, 2), dtype=np.float16)
+    with pytest.raises(RuntimeError):
+        orc.hgemm_acc16(a, b, 0)
+    assert orc.hgemm_acc16(np.ones((0, 3), np.float16), b, 16).shape == (0, 2)
+    assert np.array_equal(orc.hgemm_acc16(np.ones((2, 0), np.float16), np.ones((0, 2), np.float16), 16), np.zeros((2, 2), np.float16))
