@@ -74,7 +74,12 @@ hgemm_status_t hgemm_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K,
  * `spec` instead of the dispatch table; used by the autotuner and by tests
  * that must cover every kernel.  `spec` is a host string of the form
  *   "<family>[,key=value]..."    e.g.  "mfma,bm=256,bn=256,bk=64,st=2,sk=1"
- * Families and keys are listed by hgemm_spec_help().  A spec that cannot run
+ * Families and keys are listed by hgemm_spec_help().  One key changes the
+ * arithmetic rather than the schedule: "ac=16" asks for a 16-bit accumulator
+ * (Section 1: fp16 and fp32 accumulators are both valid for fp16 inputs;
+ * Section 2.3.2's exact-match test is built for the former): the running
+ * sums are rounded to fp16 after every 16 products.  hgemm_plan() never
+ * chooses it.  A spec that cannot run
  * the shape as it lies in memory (alignment, tile larger than the limits)
  * returns UNSUPPORTED: an explicit spec never pads.
  */

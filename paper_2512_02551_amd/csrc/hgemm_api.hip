@@ -52,6 +52,7 @@ struct Spec {
     int sm = 0;     // 1 = stream-K: whole waves of tiles data-parallel, the rest shared by K-tile iterations
     int fr = 0;     // 1 = split-K with the reduction fused into the kernel (last-arriving workgroup sums in split order)
     int ps = 0;     // 1 = persistent: one workgroup per compute unit walks the tiles without draining its copy pipeline
+    int ac = 32;    // accumulator width: 32 = fp32 over all of K; 16 = rounded to fp16 after every 16 products
 };
 
 static std::string spec_to_string(const Spec& s)
@@ -67,6 +68,7 @@ static std::string spec_to_string(const Spec& s)
     if (s.sm) strncat(buf, ",sm=1", sizeof buf - strlen(buf) - 1);
     if (s.fr) strncat(buf, ",fr=1", sizeof buf - strlen(buf) - 1);
     if (s.ps) strncat(buf, ",ps=1", sizeof buf - strlen(buf) - 1);
+    if (s.ac == 16) strncat(buf, ",ac=16", sizeof buf - strlen(buf) - 1);
     return buf;
 }
 
@@ -109,11 +111,14 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "sm") sp.sm = (int)v;
         else if (key == "fr") sp.fr = (int)v;
         else if (key == "ps") sp.ps = (int)v;
+        else if (key == "ac") sp.ac = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
     if (sp.sk < 1 || sp.tb > 1 || sp.sm > 1 || sp.fr > 1 || sp.ps > 1 || (sp.sm && sp.sk > 1) || (sp.ps && (sp.sk > 1 || sp.sm)))
         return false;
+    // the 16-bit accumulator is a running sum over all of K in k order: one tile per workgroup, no splitting of K
+    if ((sp.ac != 32 && sp.ac != 16) || (sp.ac == 16 && (sp.fam != FAM_MFMA || sp.sk > 1 || sp.sm || sp.ps || sp.fr))) return false;
     *out = sp;
     return true;
 }
@@ -555,7 +560,9 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
         hipFuncSetAttribute((const void*)e->splitk_fused, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)e->splitk_fused_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
         (e->persist && hipFuncSetAttribute((const void*)e->persist, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ||
-        (e->persist_tn && hipFuncSetAttribute((const void*)e->persist_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess)) {
+        (e->persist_tn && hipFuncSetAttribute((const void*)e->persist_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ||
+        hipFuncSetAttribute((const void*)e->acc16, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)e->acc16_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return HGEMM_ERR_LAUNCH;
     }
@@ -865,6 +872,8 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
                            (const float*)((const char*)plan->workspace + plan->partial_offset), (_Float16*)C, (int)M, (int)N,
                            (int)plan->lay.ldc, a.splits);
+    } else if (plan->spec.ac == 16) {
+        hipLaunchKernelGGL(plan->tn_kernel ? e->acc16_tn : e->acc16, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     } else {
         hipLaunchKernelGGL(plan->tn_kernel ? e->plain_tn : e->plain, dim3(wgs), dim3(e->threads), e->lds_bytes, stream, a);
     }
@@ -971,7 +980,7 @@ const char* hgemm_spec_help(void)
             "    K slab each and stream it in steps of 64 rows (loads one step ahead, transposed through LDS, 16x16x32\n"
             "    matrix-core instructions with M on a 16-wide side); slabs are summed in slab order by the split-K\n"
             "    reduction launch or, with fr = 1, inside the kernel by the workgroup that arrives last\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1]\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
             "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
@@ -982,6 +991,9 @@ const char* hgemm_spec_help(void)
             "            tile's first K-tiles start under the last K-tiles of the current one\n"
             "    sm = 1: stream-K (whole waves of tiles one per workgroup, the remaining tiles' K iterations dealt\n"
             "            evenly to one more workgroup per CU, fp32 partial tiles summed in k order by a second kernel)\n"
+            "    ac = 16: 16-bit accumulator: the running sums are rounded to fp16 after every matrix-core instruction\n"
+            "            (16 products); explicit specs only, with sk = 1 and without sm, ps, fr; never chosen by hgemm_plan,\n"
+            "            which always accumulates in fp32 over all of K\n"
             "    pad = 1 in a description: N, K or a leading dimension is not a multiple of 8 and the kernel runs on\n"
             "            zero-padded packed copies held in the plan's workspace (decided by hgemm_plan from the shape)\n"
             "    compiled (bm,bn,bk,wm,wn,st,pf):";
@@ -1076,7 +1088,7 @@ hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spe
         *us = predict_skinny_us(M, N, K, eff, s.fr != 0 && eff > 1);
         return HGEMM_OK;
     }
-    if (s.fam != FAM_MFMA || s.sm || s.tb || s.ps || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
+    if (s.fam != FAM_MFMA || s.sm || s.tb || s.ps || s.ac == 16 || !find_entry(s)) return HGEMM_ERR_UNSUPPORTED;
     const int64_t eff = effective_splits((K + s.bk - 1) / s.bk, s.sk);
     *us = predict_us(M, N, K, s.bm, s.bn, s.bk, s.wm, s.wn, s.st, s.pf, eff);
     if (s.fr && eff > 1) *us += fused_delta_us(M, N, eff);

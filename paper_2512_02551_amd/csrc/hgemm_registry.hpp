@@ -19,6 +19,8 @@ struct MfmaEntry {
     void (*splitk_fused_tn)(GemmArgs);
     void (*persist)(GemmArgs);          // null when the configuration cannot stage its epilogue in one LDS buffer
     void (*persist_tn)(GemmArgs);
+    void (*acc16)(GemmArgs);            // 16-bit accumulator variant
+    void (*acc16_tn)(GemmArgs);
     void (*fixup)(GemmArgs);
 };
 
@@ -36,6 +38,7 @@ template <class C> inline MfmaEntry make_entry()
                      mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
                      mfma_gemm_kernel<C, MODE_SPLITK_FUSED, false>, mfma_gemm_kernel<C, MODE_SPLITK_FUSED, true>,
                      persist_kernel<C, false>(), persist_kernel<C, true>(),
+                     mfma_gemm_kernel<C, MODE_ACC16, false>, mfma_gemm_kernel<C, MODE_ACC16, true>,
                      streamk_fixup_kernel<C::BM, C::BN, C::BK>};
 }
 
