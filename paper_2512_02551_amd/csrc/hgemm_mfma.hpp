@@ -358,8 +358,11 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     asm volatile("" :: "s"(g.by_tiles_n.m), "s"(g.by_tiles_n.l), "s"(g.by_band.m), "s"(g.by_band.l), "s"(g.by_rows.m),
                  "s"(g.by_rows.l), "s"(g.by_last_rows.m), "s"(g.by_last_rows.l));
 
-    // Every lambda below is force-inlined: one that stayed a call would reach the variables it captures
-    // through memory, and a buffer descriptor loaded from memory is not in the scalar registers the copies need.
+    // Every lambda below has to end up inlined: one that stayed a call would reach the variables it captures
+    // through memory, and a buffer descriptor loaded from memory is not in the scalar registers the copies need
+    // (the assembler then rejects the copy instruction, so this cannot go unnoticed).  The lambdas are kept small
+    // enough for the inliner; forcing it with always_inline, or raising its threshold, inlines before the loops are
+    // unrolled and leaves the fragment arrays of some configurations in scratch memory.
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
@@ -405,7 +408,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // which in persistent mode runs ahead of it.
     int m0, n0;        // the tile being multiplied and stored
     int lm0, ln0;      // the tile the copies read (the same one, except in persistent mode near the end of a tile)
-    auto tile_origin = [&](int id, int& tm0, int& tn0) __attribute__((always_inline)) {
+    auto tile_origin = [&](int id, int& tm0, int& tn0) {
         unsigned tm, tn;
         tile_coords((unsigned)id, g, tm, tn);
         tm0 = (int)tm * C::BM;
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     unsigned a_voff0, b_voff0;
     bool b_col_ok;
     unsigned b_voffj[RAGGED ? C::B_LOADS : 1];
-    auto set_load_tile = [&](int id) __attribute__((always_inline)) {
+    auto set_load_tile = [&](int id) {
         if (id < 0) {                      // no tile: every copy out of range
             a_voff0 = b_voff0 = OOB;
             b_col_ok = true;
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int b_kcol = k_begin + b_chunk * 8;                             // TN only: + kt*BK, compared with k_end
 
     // One wave-load of tile kt: index j < A_LOADS is an A load, the rest are B loads.
-    auto dma_one = [&](int kt, int buf, int j) __attribute__((always_inline)) {
+    auto dma_one = [&](int kt, int buf, int j) {
         char* sA = lds + buf * C::STAGE_BYTES;
         char* sB = sA + C::A_BYTES;
         if (j < C::A_LOADS) {
@@ -485,7 +488,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
         }
     };
-    auto load_tile = [&](int kt, int buf) __attribute__((always_inline)) {
+    auto load_tile = [&](int kt, int buf) {
 #pragma unroll
         for (int j = 0; j < C::LOADS; ++j) dma_one(kt, buf, j);
     };
@@ -511,7 +514,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // Fragment read number r of a k-step: r < TM reads A fragment r, the rest read B fragment r-TM.
     constexpr int NREADS = C::TM + C::TN;
     constexpr int NMMA = C::TM * C::TN;
-    auto read_one = [&](int buf, int ks, int slot, int r) __attribute__((always_inline)) {
+    auto read_one = [&](int buf, int ks, int slot, int r) {
         const char* sA = lds + buf * C::STAGE_BYTES;
         const char* sB = sA + C::A_BYTES;
         if (r < C::TM) {
@@ -535,18 +538,18 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             fb[slot][tn] = u.h;
         }
     };
-    auto read_frags = [&](int buf, int ks, int slot) __attribute__((always_inline)) {
+    auto read_frags = [&](int buf, int ks, int slot) {
 #pragma unroll
         for (int r = 0; r < NREADS; ++r) read_one(buf, ks, slot, r);
     };
-    auto mma_one = [&](int slot, int i) __attribute__((always_inline)) {
+    auto mma_one = [&](int slot, int i) {
         const int tm = i / C::TN, tn = i % C::TN;
         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
     };
     // 16-bit accumulator: the running sums are fp16 values between matrix-core instructions (round to nearest
     // even, overflow to infinity).  Every accumulator block takes exactly one instruction per k-step, so the
     // rounding is applied to all of them at the end of the k-step.
-    auto round_accumulators = [&]() __attribute__((always_inline)) {
+    auto round_accumulators = [&]() {
 #pragma unroll
         for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
@@ -561,7 +564,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // of the matrix cores instead of in a burst in front of them (the staggered prefetch of
     // Section 5.3.4, taken to instruction granularity).
     // Copies [dma_lo, dma_hi) of tile dma_kt go to buffer dma_buf.
-    auto kstep = [&](int slot, int rbuf, int rks, int rslot, bool do_reads, int dma_kt, int dma_buf, int dma_lo, int dma_hi) __attribute__((always_inline)) {
+    auto kstep = [&](int slot, int rbuf, int rks, int rslot, bool do_reads, int dma_kt, int dma_buf, int dma_lo, int dma_hi) {
         constexpr int NSIDE_MAX = NREADS + C::LOADS;
         const int nreads = do_reads ? NREADS : 0;
         const int nside = nreads + (dma_hi - dma_lo);
@@ -580,10 +583,6 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (ACC16) {
-            round_accumulators();
-            __builtin_amdgcn_sched_barrier(0);
-        }
     };
 
     // One K-tile.  Tile kt lives in LDS buffer kt % STAGES.  The k-step that runs at position ks
@@ -593,7 +592,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // tile kt+1 (copies issued STAGES-1 tiles earlier) is complete and visible to all waves.
     // WAIT = number of copies that may still be in flight at the barrier; HAS_NEXT = a next tile
     // exists; DMA = K-tile dma_kt (of the copies' tile) is copied into the vacated buffer after the barrier.
-    auto tile_body = [&](int dma_kt, int buf, int nbuf, auto wait_tag, auto has_next_tag, auto dma_tag) __attribute__((always_inline)) {
+    auto tile_body = [&](int dma_kt, int buf, int nbuf, auto wait_tag, auto has_next_tag, auto dma_tag) {
         constexpr int WAIT = decltype(wait_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool DMA = decltype(dma_tag)::value;
@@ -611,6 +610,10 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             const int dhi = (DMA && after) ? ((j + 1) * C::LOADS) / C::PF : 0;
             kstep(ks % C::NSLOT, in_next ? nbuf : buf, in_next ? t - C::KS : t, t % C::NSLOT, in_next ? HAS_NEXT : true,
                   dma_kt, buf, dlo, dhi);
+            if (ACC16) {
+                round_accumulators();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
     using std::integral_constant;
