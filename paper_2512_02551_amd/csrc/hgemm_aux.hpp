@@ -27,10 +27,11 @@ __global__ __launch_bounds__(256) void generic_gemm_kernel(const _Float16* __res
 }
 
 // Split-K second pass: C[m][n] = fp16( partial[0][m][n] + partial[1][m][n] + ... ) summed in
-// split order, so the result does not depend on which workgroup finished first.  A separate
-// launch on purpose: a reduction fused into the main kernel behind device-scope fences (last
-// arriving workgroup sums) was measured slower -- every workgroup's release fence writes back
-// its XCD's L2 -- than the few microseconds of a second launch.
+// split order, so the result does not depend on which workgroup finished first.  (The same sum can
+// be taken inside the main kernel by the workgroup that arrives last at a tile -- the fused mode --
+// which pays off only for small planes; this launch uses the whole chip for the reduction.  32-bit
+// index arithmetic and branch-free loads were tried here and changed nothing: the kernel's few
+// microseconds are the dependent launch and one trip to memory.)
 // One thread handles 4 consecutive n.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, _Float16* __restrict__ C,
                                                             int M, int N, int ldc, int splits)
