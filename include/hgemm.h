@@ -15,8 +15,10 @@
  * shape up in a table of measured choices and falls back to a fitted cost model.
  *
  * Threading: functions are thread-compatible (no global mutable state apart
- * from a read-only table); a single plan must not be run on two streams at
- * once because split-K, stream-K and padded plans own a workspace.
+ * from a read-only table and two per-device caches behind mutexes: whether a
+ * device is a gfx950, and the address of hgemm_run_static's scratch array); a
+ * single plan must not be run on two streams at once because split-K,
+ * stream-K and padded plans own a workspace.
  * The library never prints, never throws, never synchronises the device, and
  * launches only on the stream it is given (Section 2.4.1 forbids a kernel
  * under test from using extra streams).
