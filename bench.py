@@ -434,7 +434,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build measures one GPU only (asked for --gpus {args.gpus}); "
-              "the library has no multi-GPU path, see DESIGN.md", file=sys.stderr)
+              "the library has no multi-GPU path (each GPU would run it on its own block of C)", file=sys.stderr)
         sys.exit(2)
 
     if args.workload == "P":
