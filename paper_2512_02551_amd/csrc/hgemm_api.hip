@@ -441,6 +441,7 @@ bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out, bool b_row_major =
         }
     }
     for (const MfmaEntry& e : registry()) {
+        if (e.deep) continue;                        // the cost model was not fitted to deep-staged kernels: the tuner's business
         if (!tile_fits_problem(e, M, N)) continue;
         const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
         const int64_t ktiles = (K + e.bk - 1) / e.bk;
@@ -550,21 +551,19 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     if (s.tb && p->lay.b != HGEMM_ROW_MAJOR) return HGEMM_ERR_UNSUPPORTED;
     p->tn_kernel = s.tb || p->lay.b == HGEMM_COL_MAJOR;
     p->entry = e;
+    // deep-staged configurations exist for one full-K tile per workgroup only
+    if (e->deep && (s.sk > 1 || s.sm || s.ps || s.fr || s.ac == 16)) return HGEMM_ERR_UNSUPPORTED;
     // dynamic LDS beyond 64 KiB has to be requested per kernel function
-    if (hipFuncSetAttribute((const void*)e->plain, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->plain_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->streamk, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->streamk_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk_fused, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->splitk_fused_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        (e->persist && hipFuncSetAttribute((const void*)e->persist, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ||
-        (e->persist_tn && hipFuncSetAttribute((const void*)e->persist_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ||
-        hipFuncSetAttribute((const void*)e->acc16, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)e->acc16_tn, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return HGEMM_ERR_LAUNCH;
+    {
+        void (*const kernels[])(GemmArgs) = {e->plain, e->splitk, e->plain_tn, e->splitk_tn, e->streamk, e->streamk_tn, e->splitk_fused,
+                                             e->splitk_fused_tn, e->persist, e->persist_tn, e->acc16, e->acc16_tn};
+        bool ok = true;
+        for (auto k : kernels)
+            if (k && hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess) ok = false;
+        if (!ok) {
+            (void)hipGetLastError();
+            return HGEMM_ERR_LAUNCH;
+        }
     }
     GemmArgs& a = p->args;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
@@ -998,6 +997,17 @@ const char* hgemm_spec_help(void)
             "            zero-padded packed copies held in the plan's workspace (decided by hgemm_plan from the shape)\n"
             "    compiled (bm,bn,bk,wm,wn,st,pf):";
         for (const MfmaEntry& e : registry()) {
+            if (e.deep) continue;
+            char b[64];
+            snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
+            t += b;
+        }
+        t += "\n"
+             "    deep-staged, pf longer than a K-tile (bk = 32, pf = 3: fragment reads run up to two K-tiles ahead, st stages of\n"
+             "    32 k each keep st - 1 K-tiles of copies in flight); one full-K tile per workgroup only: sk = 1, no sm, ps, fr, ac\n"
+             "    deep (bm,bn,bk,wm,wn,st,pf):";
+        for (const MfmaEntry& e : registry()) {
+            if (!e.deep) continue;
             char b[64];
             snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
             t += b;
@@ -1035,6 +1045,17 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
             if (!tile_fits_problem(e, M, N)) continue;
             const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
             const int64_t ktiles = (K + e.bk - 1) / e.bk;
+            if (e.deep) {                                       // one full-K tile per workgroup; worth timing once the chip is full
+                if (t < CUS / 2 || ktiles < 2 * e.st) continue;
+                for (int gm : {8, 0, 4, 16}) {
+                    if (gm != 8 && (t < 2 * CUS)) continue;
+                    Spec s;
+                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = 1; s.gm = gm;
+                    out += spec_to_string(s);
+                    out += "\n";
+                }
+                continue;
+            }
             const std::vector<int> sks = split_candidates(t, ktiles);
             if (t % CUS != 0 && ktiles >= 4 && e.bm >= 64 && e.bn >= 64) {
                 Spec s;

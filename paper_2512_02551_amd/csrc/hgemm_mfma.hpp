@@ -274,8 +274,13 @@ struct MfmaCfg {
     static constexpr bool CAN_PERSIST = NWAVES * 32 * (WTN * 2 + 8) <= STAGE_BYTES;
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
-    static_assert(KS % NSLOT == 0, "the k-steps of a tile must cycle through the fragment sets a whole number of times");
-    static_assert(PF >= 1 && PF <= KS, "prefetch distance");
+    // Deep staging: a prefetch distance longer than a K-tile.  BK = 32 (two k-steps per K-tile) with PF = 3: the
+    // fragment reads run three k-steps, i.e. up to two K-tiles, ahead of the matrix cores, the four fragment
+    // sets cycle once per two K-tiles, and five 32 KiB stages keep four K-tiles of copies in flight -- twice the
+    // lead of two 64 KiB stages in the same LDS.  One tile per workgroup only (no split-K, stream-K, persistence).
+    static constexpr bool DEEP = PF > KS;
+    static_assert(DEEP ? (KS == 2 && PF == 3 && STAGES >= 4)
+                       : (KS % NSLOT == 0 && PF >= 1), "the k-steps must cycle through the fragment sets a whole number of times");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into wave loads");
     static_assert(BN >= 64 && BN <= 512, "BN");
     static_assert((NWAVES * A_RPI) % 16 == 0, "A swizzle must be periodic in the rows one round of loads covers");
@@ -348,6 +353,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     constexpr bool STREAMK = MODE == MODE_STREAMK;
     constexpr bool PERSIST = MODE == MODE_PERSIST;
     constexpr bool ACC16 = MODE == MODE_ACC16;
+    constexpr bool DEEP = C::DEEP;
+    static_assert(!DEEP || MODE == MODE_PLAIN, "deep-staged configurations run one full-K tile per workgroup");
     static_assert(!PERSIST || C::CAN_PERSIST, "epilogue staging must fit in one stage");
 
     // All arguments the set-up reads are pulled into scalar registers here, in one batch of loads:
@@ -621,7 +628,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     // ---- main loop ----------------------------------------------------------
     int buf = 0;                      // LDS buffer of the K-tile being multiplied
     bool has_next = false;            // persistent mode: this workgroup has another tile after this one
-    if (KT > 0) {
+    if (!DEEP && KT > 0) {
 #pragma unroll
         for (int s = 0; s < C::STAGES; ++s)
             if (s < KT) load_tile(s, s);
@@ -629,7 +636,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         if (KT >= C::STAGES) wait_vmcnt<(C::STAGES - 1) * C::LOADS>(); else wait_vmcnt<0>();
         asm volatile("s_barrier" ::: "memory");
 #pragma unroll
-        for (int ks = 0; ks < C::PF; ++ks) read_frags(0, ks, ks);
+        for (int ks = 0; ks < (DEEP ? 0 : C::PF); ++ks) read_frags(0, ks, ks);
         __builtin_amdgcn_sched_barrier(0);
     }
   for (;;) {       // one pass per tile of this workgroup; a single pass unless MODE_PERSIST
@@ -639,7 +646,49 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         for (int j = 0; j < C::TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    if (KT > 0) {
+    if constexpr (DEEP) {
+        // Deep-staged main loop.  The reads lead the matrix cores by three k-steps; "the read tile" is the K-tile
+        // the reads are in.  When the reads move on to the next K-tile: that tile must have landed (all copies but
+        // those of the STAGES - 2 younger tiles), every wave must be done reading the tile they leave (its buffer
+        // is refilled next), one barrier covers both.  Every pass issues the same number of copies -- K-tiles
+        // past the end are copied out of range, which moves zeros -- so the waits are compile-time constants, and
+        // an odd number of K-tiles is rounded up with a tile of zeros so that the fragment sets cycle evenly.
+        constexpr int S = C::STAGES, L = C::LOADS;
+        static_assert((S - 1) * L <= 63 && L % 2 == 0, "vmcnt range; copies are issued in two halves");
+        int rt = 0, rb = 0;                  // read tile and its buffer
+        int dkt = 0, dbuf = 0;               // the refill in progress: K-tile dkt into buffer dbuf
+        auto enter_next_tile = [&]() {
+            wait_vmcnt<(S - 2) * L>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            dkt = rt + S;
+            dbuf = rb;
+            rt += 1;
+            rb = (rb + 1 == S) ? 0 : rb + 1;
+        };
+#pragma unroll
+        for (int s0 = 0; s0 < S; ++s0) load_tile(s0, s0);
+        wait_vmcnt<(S - 1) * L>();
+        asm volatile("s_barrier" ::: "memory");
+        read_frags(0, 0, 0);
+        read_frags(0, 1, 1);
+        enter_next_tile();
+#pragma unroll
+        for (int j = 0; j < L / 2; ++j) dma_one(dkt, dbuf, j);     // K-tile S into the buffer K-tile 0 has left, first half
+        read_frags(rb, 0, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        const int KT2 = (KT + 1) & ~1;
+        // One pass = two K-tiles = four k-steps; k-step u multiplies fragment set u and reads the k-step three
+        // ahead into set (u + 3) % 4.  A refill is issued in two halves: behind the barrier, and in the k-step after.
+        for (int t2 = 0; t2 < KT2; t2 += 2) {
+            kstep(0, rb, 1, 3, true, dkt, dbuf, L / 2, L);
+            enter_next_tile();
+            kstep(1, rb, 0, 0, true, dkt, dbuf, 0, L / 2);
+            kstep(2, rb, 1, 1, true, dkt, dbuf, L / 2, L);
+            enter_next_tile();
+            kstep(3, rb, 0, 2, true, dkt, dbuf, 0, L / 2);
+        }
+        wait_vmcnt<0>();                     // copies still in flight would land in the epilogue's staging area
+    } else if (KT > 0) {
         constexpr int STEADY = (C::STAGES - 2) * C::LOADS;
         int kt = 0;
         if (PERSIST) {

@@ -9,6 +9,7 @@ namespace hgemm {
 struct MfmaEntry {
     int bm, bn, bk, wm, wn, st, pf;
     int threads, lds_bytes;
+    bool deep;                          // deep-staged configuration: only the one-tile-per-workgroup kernels exist
     void (*plain)(GemmArgs);
     void (*splitk)(GemmArgs);
     void (*plain_tn)(GemmArgs);
@@ -32,14 +33,23 @@ template <class C, bool TN> inline void (*persist_kernel())(GemmArgs)
 
 template <class C> inline MfmaEntry make_entry()
 {
-    return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::PF, C::THREADS, C::LDS_BYTES,
-                     mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
-                     mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
-                     mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
-                     mfma_gemm_kernel<C, MODE_SPLITK_FUSED, false>, mfma_gemm_kernel<C, MODE_SPLITK_FUSED, true>,
-                     persist_kernel<C, false>(), persist_kernel<C, true>(),
-                     mfma_gemm_kernel<C, MODE_ACC16, false>, mfma_gemm_kernel<C, MODE_ACC16, true>,
-                     streamk_fixup_kernel<C::BM, C::BN, C::BK>};
+    if constexpr (C::DEEP) {
+        MfmaEntry e{};
+        e.bm = C::BM; e.bn = C::BN; e.bk = C::BK; e.wm = C::WAVES_M; e.wn = C::WAVES_N; e.st = C::STAGES; e.pf = C::PF;
+        e.threads = C::THREADS; e.lds_bytes = C::LDS_BYTES; e.deep = true;
+        e.plain = mfma_gemm_kernel<C, MODE_PLAIN, false>;
+        e.plain_tn = mfma_gemm_kernel<C, MODE_PLAIN, true>;
+        return e;
+    } else {
+        return MfmaEntry{C::BM, C::BN, C::BK, C::WAVES_M, C::WAVES_N, C::STAGES, C::PF, C::THREADS, C::LDS_BYTES, false,
+                         mfma_gemm_kernel<C, MODE_PLAIN, false>, mfma_gemm_kernel<C, MODE_SPLITK, false>,
+                         mfma_gemm_kernel<C, MODE_PLAIN, true>, mfma_gemm_kernel<C, MODE_SPLITK, true>,
+                         mfma_gemm_kernel<C, MODE_STREAMK, false>, mfma_gemm_kernel<C, MODE_STREAMK, true>,
+                         mfma_gemm_kernel<C, MODE_SPLITK_FUSED, false>, mfma_gemm_kernel<C, MODE_SPLITK_FUSED, true>,
+                         persist_kernel<C, false>(), persist_kernel<C, true>(),
+                         mfma_gemm_kernel<C, MODE_ACC16, false>, mfma_gemm_kernel<C, MODE_ACC16, true>,
+                         streamk_fixup_kernel<C::BM, C::BN, C::BK>};
+    }
 }
 
 void register_chunk_0(std::vector<MfmaEntry>& out);

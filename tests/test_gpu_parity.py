@@ -210,6 +210,50 @@ def test_persistent_mode_every_capable_spec_bit_exact():
         assert np.array_equal(p1.view(np.uint16), p2.view(np.uint16)) and np.array_equal(p1.view(np.uint16), plain.view(np.uint16)), desc
 
 
+def deep_specs(gm=8):
+    out = []
+    for line in hg.spec_help().splitlines():
+        if line.strip().startswith("deep (bm"):
+            for tup in line.split(":")[1].split():
+                bm, bn, bk, wm, wn, st, pf = (int(x) for x in tup.strip("()").split(","))
+                out.append(f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},pf={pf},sk=1,gm={gm}")
+    assert out
+    return out
+
+
+@pytest.mark.parametrize("shape", [(300, 264, 200), (257, 520, 328), (512, 512, 40), (260, 304, 8), (520, 264, 2056), (1030, 1544, 96)])
+def test_deep_staged_specs_bit_exact_on_ragged_shapes_both_layouts(shape):
+    """Deep-staged configurations (prefetch distance longer than a K-tile): fragment reads run up to two K-tiles ahead
+    of the matrix cores and K-tiles past the end are copied as zeros.  K gives an odd and an even number of K-tiles,
+    fewer K-tiles than stages (40, 8), a last K-tile of 8 (200, 328, 40, 8, 2056); M and N are ragged; several tiles per
+    compute unit in the last shape."""
+    name, a, b = wl.exact_family_for(shape, seed=71)
+    ref = orc.hgemm(a, b)
+    bt = np.ascontiguousarray(b.T)
+    for spec in deep_specs() + deep_specs(gm=0):
+        c, before, after, desc = run_hgemm(a, b, spec=spec, guard=2)
+        assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all(), desc
+        c, _, _, desc = run_hgemm(a, bt, spec=spec, b_col_major=True)
+        assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
+
+
+def test_deep_staged_specs_real_inputs_repeatable_and_refusals():
+    shape = (520, 776, 4104)
+    rng = np.random.default_rng(72)
+    a = wl.uniform_pm1(rng, shape[0], shape[2])
+    b = wl.uniform_pm1(rng, shape[2], shape[1])
+    ref = orc.hgemm(a, b)
+    for spec in deep_specs():
+        c1, _, _, desc = run_hgemm(a, b, spec=spec)
+        c2, _, _, _ = run_hgemm(a, b, spec=spec)
+        assert_close(c1, ref, desc)
+        assert np.array_equal(c1.view(np.uint16), c2.view(np.uint16)), desc
+        for bad in (spec.replace("sk=1", "sk=2"), spec + ",sm=1", spec + ",ps=1", spec + ",ac=16", spec.replace("sk=1", "sk=2") + ",fr=1"):
+            with pytest.raises(hg.HgemmError):
+                hg.Plan(*shape, None, bad)
+
+
 def test_server_mode_idle_gaps_between_calls():
     """Server mode (Section 2.4.2): the device idles for a random 0-2 ms before every call, caches and clocks cool
     down in between.  Every call of a plan, whatever its kind (single kernel, two-launch split-K, fused split-K
