@@ -654,7 +654,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         // past the end are copied out of range, which moves zeros -- so the waits are compile-time constants, and
         // an odd number of K-tiles is rounded up with a tile of zeros so that the fragment sets cycle evenly.
         constexpr int S = C::STAGES, L = C::LOADS;
-        static_assert((S - 1) * L <= 63 && L % 2 == 0, "vmcnt range; copies are issued in two halves");
+        static_assert((S - 1) * L <= 63, "vmcnt range");
         int rt = 0, rb = 0;                  // read tile and its buffer
         int dkt = 0, dbuf = 0;               // the refill in progress: K-tile dkt into buffer dbuf
         auto enter_next_tile = [&]() {
