@@ -50,21 +50,21 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); figures and commands in profiles/.  Reported as
 # roofline.traffic with roofline.traffic_source saying so.
 PROFILED_TRAFFIC_BYTES = {
-    (1024, 1024, 1024): (6188.0 * 2.0 + 2048.0) * 1024,
-    (2048, 2048, 2048): (24611.0 * 2.0 + 8192.0) * 1024,
-    (4096, 4096, 4096): (98564.5 * 2.0 + 33024.0) * 1024,
-    (8192, 8192, 8192): (787155.6 * 2.0 + 132096.0) * 1024,
-    (16384, 16384, 8192): (3209252.6 * 2.0 + 524288.0) * 1024,
-    (16384, 16384, 16384): (7109019.1 * 2.0 + 524288.0) * 1024,
+    (1024, 1024, 1024): (6183.0 * 2.0 + 2048.0) * 1024,
+    (2048, 2048, 2048): (24632.5 * 2.0 + 8192.0) * 1024,
+    (4096, 4096, 4096): (98572.8 * 2.0 + 33024.0) * 1024,
+    (8192, 8192, 8192): (787208.1 * 2.0 + 132096.0) * 1024,
+    (16384, 16384, 8192): (3152504.8 * 2.0 + 528384.0) * 1024,
+    (16384, 16384, 16384): (6820277.9 * 2.0 + 528384.0) * 1024,
     # cold skinny shapes (the HBM roofline's candidates); sums over the kernels of one call
     (1, 4096, 4096): (16497.8 * 2.0 + 146.0) * 1024,
-    (16, 4096, 4096): (17723.8 * 2.0 + 1664.0) * 1024,
-    (1, 11008, 4096): (44214.4 * 2.0 + 372.2) * 1024,
-    (16, 11008, 4096): (45986.5 * 2.0 + 3096.0) * 1024,
-    (1, 4096, 11008): (44201.6 * 2.0 + 146.0) * 1024,
+    (16, 4096, 4096): (17723.9 * 2.0 + 1664.0) * 1024,
+    (1, 11008, 4096): (44214.2 * 2.0 + 372.2) * 1024,
+    (16, 11008, 4096): (45993.9 * 2.0 + 3096.0) * 1024,
+    (1, 4096, 11008): (44201.4 * 2.0 + 146.0) * 1024,
     (16, 4096, 11008): (45982.9 * 2.0 + 1152.0) * 1024,
-    (1, 14336, 4096): (57415.3 * 2.0 + 28.0) * 1024,
-    (16, 14336, 4096): (57895.2 * 2.0 + 448.0) * 1024,
+    (1, 14336, 4096): (57415.0 * 2.0 + 28.0) * 1024,
+    (16, 14336, 4096): (57895.1 * 2.0 + 448.0) * 1024,
 }
 
 
