@@ -52,19 +52,19 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PROFILED_TRAFFIC_BYTES = {
     (1024, 1024, 1024): (6183.0 * 2.0 + 2048.0) * 1024,
     (2048, 2048, 2048): (24632.5 * 2.0 + 8192.0) * 1024,
-    (4096, 4096, 4096): (98572.8 * 2.0 + 33024.0) * 1024,
-    (8192, 8192, 8192): (787208.1 * 2.0 + 132096.0) * 1024,
-    (16384, 16384, 8192): (3152504.8 * 2.0 + 528384.0) * 1024,
-    (16384, 16384, 16384): (6820277.9 * 2.0 + 528384.0) * 1024,
+    (4096, 4096, 4096): (98573.4 * 2.0 + 33024.0) * 1024,
+    (8192, 8192, 8192): (787123.8 * 2.0 + 132096.0) * 1024,
+    (16384, 16384, 8192): (3153604.3 * 2.0 + 528384.0) * 1024,
+    (16384, 16384, 16384): (6846089.4 * 2.0 + 528384.0) * 1024,
     # cold skinny shapes (the HBM roofline's candidates); sums over the kernels of one call
-    (1, 4096, 4096): (16497.8 * 2.0 + 146.0) * 1024,
-    (16, 4096, 4096): (17723.9 * 2.0 + 1664.0) * 1024,
-    (1, 11008, 4096): (44214.2 * 2.0 + 372.2) * 1024,
-    (16, 11008, 4096): (45993.9 * 2.0 + 3096.0) * 1024,
-    (1, 4096, 11008): (44201.4 * 2.0 + 146.0) * 1024,
+    (1, 4096, 4096): (16498.5 * 2.0 + 146.0) * 1024,
+    (16, 4096, 4096): (17724.5 * 2.0 + 1664.0) * 1024,
+    (1, 11008, 4096): (44214.3 * 2.0 + 372.2) * 1024,
+    (16, 11008, 4096): (45994.0 * 2.0 + 3096.0) * 1024,
+    (1, 4096, 11008): (44201.7 * 2.0 + 146.0) * 1024,
     (16, 4096, 11008): (45982.9 * 2.0 + 1152.0) * 1024,
-    (1, 14336, 4096): (57415.0 * 2.0 + 28.0) * 1024,
-    (16, 14336, 4096): (57895.1 * 2.0 + 448.0) * 1024,
+    (1, 14336, 4096): (57415.5 * 2.0 + 28.0) * 1024,
+    (16, 14336, 4096): (57895.3 * 2.0 + 448.0) * 1024,
 }
 
 
@@ -91,6 +91,10 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the roofline calibration kernels (MFMA-only loop, 1 GiB streaming read, "
                          "128 MiB fill) -- kernels of known size for scaling profiler counters")
+    ap.add_argument("--order", choices=["flop", "listed"], default="flop",
+                    help="default run: order of the shapes inside a step -- by ascending 2*M*N*K, so that a shape runs after "
+                         "shapes of similar power draw (the chip carries a large problem's throttled clock into the next "
+                         "milliseconds), or as the workloads list them")
     ap.add_argument("--graph", action="store_true",
                     help="capture each shape's K back-to-back calls in a HIP graph and time its replay: removes the "
                          "host's enqueue rate (about 3.4 us per call from Python) from launch-bound small shapes")
@@ -269,6 +273,8 @@ def metric_run(args):
 
     jobs = [("C4", s, False) for s in wl.c4_shapes()] + [("C2", s, False) for s in wl.C2_SHAPES] + \
            [("C5", s, False) for s in wl.C5_SHAPES] + [("C3", s, True) for s in wl.C3_SHAPES]
+    if args.order == "flop":
+        jobs.sort(key=lambda j: 2.0 * j[1][0] * j[1][1] * j[1][2])     # stable: equal sizes keep their listed order
     sets = []
     for (cfg, (M, N, K), cold) in jobs:
         a, b = wl.device_inputs(cfg, (M, N, K))
@@ -414,6 +420,7 @@ def metric_run(args):
             "workload": "C4: 200-shape grid sampled with seed 1 from {64..12288}^3, uniform[-1,1] (the value); timed in the "
                         "same steps: C2 square sweep and C5 16384^2 x {8192,16384} warm, C3 LLM skinny shapes from HBM (cold)",
             "layout": "NN row-major", "cache": "warm (C3: cold, rotating operand sets > 768 MiB)",
+            "order": "shapes by ascending 2*M*N*K" if args.order == "flop" else "shapes as the workloads list them",
             "timing": (f"{steps} back-to-back calls per shape in {n_batches} batches, an event on the launch stream between batches; " +
                        ("each batch captured once in a HIP graph and replayed" if args.graph else "calls enqueued one by one from the host")),
             "aggregate_tflops": sum(2.0 * r["shape"][0] * r["shape"][1] * r["shape"][2] for r in per_shape) * steps / wall * 1e-12,
