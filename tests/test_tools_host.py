@@ -75,3 +75,18 @@ def test_bench_workload_tables():
         shapes, gen = bench.workload_shapes(name)
         assert len(shapes) == count
     assert bench.PEAK_FP16_TFLOPS == 2500.0 and bench.PEAK_HBM_GBS == 8000.0
+
+
+def test_bench_defaults_and_profiled_traffic_cover_the_roofline_shapes(monkeypatch):
+    """The default run sorts a step's shapes by work, and every shape that can become `roofline` (the largest
+    compute-bound one) or `roofline_hbm` (the memory-bound skinny ones with M <= 16) has a profiled traffic figure
+    at least as large as its algorithmic bytes."""
+    import bench
+    import workloads as wl
+    monkeypatch.setattr(sys, "argv", ["bench.py"])
+    args = bench.parse_args()
+    assert args.order == "flop" and args.gpus == 1
+    need = [max(wl.C5_SHAPES, key=lambda s: s[0] * s[1] * s[2])] + [s for s in wl.C3_SHAPES if s[0] <= 16]
+    for (M, N, K) in need:
+        assert (M, N, K) in bench.PROFILED_TRAFFIC_BYTES, (M, N, K)
+        assert bench.PROFILED_TRAFFIC_BYTES[(M, N, K)] >= 2.0 * (M * K + K * N + M * N) * 0.98
