@@ -16,7 +16,7 @@ CSRC = os.path.join(_HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(_HERE, "libhgemm.so")
 HEADERS = [os.path.join(CSRC, n) for n in ("hgemm_mfma.hpp", "hgemm_aux.hpp", "hgemm_registry.hpp", "hgemm_configs.inc",
-                                           "hgemm_skinny.hpp", "dispatch_table.inc", "plan_model.inc")] + [os.path.join(os.path.dirname(_HERE), "include", "hgemm.h")]
+                                           "hgemm_skinny.hpp", "dispatch_table.inc", "dispatch_table_tn.inc", "plan_model.inc")] + [os.path.join(os.path.dirname(_HERE), "include", "hgemm.h")]
 API_SRC = os.path.join(CSRC, "hgemm_api.hip")
 KERNEL_SRC = os.path.join(CSRC, "hgemm_kernels.hip")
 SKINNY_SRC = os.path.join(CSRC, "hgemm_skinny.hip")

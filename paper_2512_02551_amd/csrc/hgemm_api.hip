@@ -255,9 +255,17 @@ Spec heuristic(int64_t M, int64_t N, int64_t K)
 }
 
 #include "dispatch_table.inc"
+#include "dispatch_table_tn.inc"
 
-bool table_lookup(int64_t M, int64_t N, int64_t K, Spec* out)
+// The measured row for a shape: with column-major B the table tuned in that layout first, then (as for
+// row-major B) the table tuned with row-major B, whose tile sizes and split factors carry over.
+bool table_lookup(int64_t M, int64_t N, int64_t K, bool b_col_major, Spec* out)
 {
+    if (b_col_major)
+        for (size_t i = 0; i < sizeof(kDispatchTableTN) / sizeof(kDispatchTableTN[0]); ++i) {
+            const DispatchRow& r = kDispatchTableTN[i];
+            if (r.m == M && r.n == N && r.k == K && r.spec[0] != '\0' && parse_spec(r.spec, out)) return true;
+        }
     for (size_t i = 0; i < sizeof(kDispatchTable) / sizeof(kDispatchTable[0]); ++i) {
         const DispatchRow& r = kDispatchTable[i];
         if (r.m == M && r.n == N && r.k == K) return r.spec[0] != '\0' && parse_spec(r.spec, out);
@@ -711,7 +719,7 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
             st = finish_plan(p);
         } else {
             const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
-            if (!table_lookup(M, N, K, &p->spec) || !packed) {
+            if (!table_lookup(M, N, K, l.b == HGEMM_COL_MAJOR, &p->spec) || !packed) {
                 if (!model_choice(M, N, K, &p->spec, l.b == HGEMM_ROW_MAJOR)) p->spec = heuristic(M, N, K);
             }
             if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already

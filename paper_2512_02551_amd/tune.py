@@ -33,6 +33,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE = os.path.join(_HERE, "csrc", "dispatch_table.inc")
 DEFAULT_LOG = os.path.join(_HERE, "csrc", "dispatch_tuning_log.jsonl")
+# B column-major (the paper's TN layout, Section 3): a table of its own, for the shapes tuned in that layout
+TABLE_TN = os.path.join(_HERE, "csrc", "dispatch_table_tn.inc")
+DEFAULT_LOG_TN = os.path.join(_HERE, "csrc", "dispatch_tuning_log_tn.jsonl")
 
 
 def all_shapes(workloads):
@@ -62,6 +65,7 @@ def all_shapes(workloads):
 
 
 def write_table(log_path: str, table_path: str = TABLE) -> int:
+    tn = os.path.basename(table_path) == os.path.basename(TABLE_TN)
     rows = {}
     if os.path.exists(log_path):
         with open(log_path) as f:
@@ -71,12 +75,18 @@ def write_table(log_path: str, table_path: str = TABLE) -> int:
                     r = json.loads(line)
                     rows[tuple(r["shape"])] = r
     with open(table_path, "w") as f:
-        f.write("// Per-shape dispatch table: (M, N, K) -> specialisation, filled from timed runs on one MI355X\n"
-                "// by the autotuner (python -m paper_2512_02551_amd.tune).  An empty spec means \"use the cost model\".\n"
-                "// Columns of the trailing comment: median microseconds, TFLOP/s, GB/s of algorithmic traffic.\n"
-                "struct DispatchRow { int64_t m, n, k; const char* spec; };\n"
-                "static const DispatchRow kDispatchTable[] = {\n"
-                "    {0, 0, 0, \"\"},\n")
+        if tn:
+            f.write("// Per-shape dispatch table for column-major B (the TN layout): same form as dispatch_table.inc, filled by\n"
+                    "// python -m paper_2512_02551_amd.tune --layout tn.  Shapes it does not hold use the row of the NN table.\n"
+                    "static const DispatchRow kDispatchTableTN[] = {\n"
+                    "    {0, 0, 0, \"\"},\n")
+        else:
+            f.write("// Per-shape dispatch table: (M, N, K) -> specialisation, filled from timed runs on one MI355X\n"
+                    "// by the autotuner (python -m paper_2512_02551_amd.tune).  An empty spec means \"use the cost model\".\n"
+                    "// Columns of the trailing comment: median microseconds, TFLOP/s, GB/s of algorithmic traffic.\n"
+                    "struct DispatchRow { int64_t m, n, k; const char* spec; };\n"
+                    "static const DispatchRow kDispatchTable[] = {\n"
+                    "    {0, 0, 0, \"\"},\n")
         for (m, n, k) in sorted(rows):
             r = rows[(m, n, k)]
             f.write(f"    {{{m}, {n}, {k}, \"{r['spec']}\"}},  // {r['median_us']:.1f} us, {r['tflops']:.1f} TFLOP/s, {r['gbs']:.0f} GB/s\n")
@@ -87,7 +97,10 @@ def write_table(log_path: str, table_path: str = TABLE) -> int:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workloads", default="C1,C2,C3,C4,C5")
-    ap.add_argument("--out-log", default=DEFAULT_LOG)
+    ap.add_argument("--layout", choices=["nn", "tn"], default="nn",
+                    help="tn: B column-major (stored N x K); candidates, gate and timing use that layout and the result goes "
+                         "to the TN log and table")
+    ap.add_argument("--out-log", default="", help="default: the committed log of the layout")
     ap.add_argument("--resume", action="store_true")
     ap.add_argument("--coarse", type=int, default=7)
     ap.add_argument("--fine", type=int, default=30)
@@ -120,13 +133,17 @@ def main():
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
                          "so that the choice is made for data coming from HBM, not from the last-level cache")
     args = ap.parse_args()
+    tn = args.layout == "tn"
+    table = TABLE_TN if tn else TABLE
+    if not args.out_log:
+        args.out_log = DEFAULT_LOG_TN if tn else DEFAULT_LOG
 
     if args.combine:
         print("rows changed:", combine_passes([p for p in args.combine.split(",") if p], args.out_log))
-        print("rows:", write_table(args.out_log))
+        print("rows:", write_table(args.out_log, table))
         return
     if args.table_only:
-        print("rows:", write_table(args.out_log))
+        print("rows:", write_table(args.out_log, table))
         return
 
     import torch
@@ -137,6 +154,7 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
+    lay = hg.Layouts.make(b_col_major=True) if tn else None
 
     done = set()
     if args.resume and os.path.exists(args.out_log):
@@ -233,6 +251,8 @@ def main():
         b = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).half()
         ai = torch.randint(-2, 3, (M, K), device="cuda", generator=gen).half()
         bi = torch.randint(-2, 3, (K, N), device="cuda", generator=gen).half()
+        if tn:                                    # the same matrices, stored N x K
+            b, bi = b.t().contiguous(), bi.t().contiguous()
         c = torch.empty((M, N), device="cuda", dtype=torch.float16)
         cref = torch.empty((M, N), device="cuda", dtype=torch.float16)
         rot["sets"] = None
@@ -249,22 +269,22 @@ def main():
         full_gate = M * N * K <= 2 ** 37
         bands = []
         if full_gate:
-            with hg.Plan(M, N, K, None, "generic") as p:
+            with hg.Plan(M, N, K, lay, "generic") as p:
                 p.run(ai.data_ptr(), bi.data_ptr(), cref.data_ptr(), sh)
                 torch.cuda.synchronize()
         else:
             for r0 in sorted({0, (M // 2) // 16 * 16, max(0, M - 16)}):
                 rows = min(16, M - r0)
                 band = torch.empty((rows, N), device="cuda", dtype=torch.float16)
-                with hg.Plan(rows, N, K, None, "generic") as p:
+                with hg.Plan(rows, N, K, lay, "generic") as p:
                     p.run(ai[r0:r0 + rows].data_ptr(), bi.data_ptr(), band.data_ptr(), sh)
                     torch.cuda.synchronize()
                 bands.append((r0, rows, band))
         plans = []
         rejected = 0
-        for spec in (recorded.get((M, N, K)) or hg.candidates(M, N, K)):
+        for spec in (recorded.get((M, N, K)) or hg.candidates(M, N, K, lay)):
             try:
-                p = hg.Plan(M, N, K, None, spec)
+                p = hg.Plan(M, N, K, lay, spec)
             except hg.HgemmError:
                 continue
             c.fill_(float("nan"))
@@ -329,9 +349,9 @@ def main():
         del a, b, ai, bi, c, cref
     if args.merge_into:
         merge_logs(args.merge_into, args.out_log)
-        print("rows:", write_table(args.merge_into), flush=True)
+        print("rows:", write_table(args.merge_into, table), flush=True)
     else:
-        print("rows:", write_table(args.out_log), flush=True)
+        print("rows:", write_table(args.out_log, table), flush=True)
 
 
 def combine_passes(paths, main_log: str) -> int:

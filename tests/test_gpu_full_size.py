@@ -151,3 +151,32 @@ def test_extreme_aspect_ratios(shape):
     assert np.array_equal(c[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {name} {desc}"
     assert np.isnan(before).all() and np.isnan(after).all(), desc
     print(f"{shape}: {desc}")
+
+
+def _tn_table():
+    import json
+    import os
+    path = os.path.join(os.path.dirname(hg.__file__), "csrc", "dispatch_tuning_log_tn.jsonl")
+    return {tuple(r["shape"]): r["spec"] for r in (json.loads(line) for line in open(path) if line.strip())}
+
+
+@pytest.mark.parametrize("shape", [*wl.C2_SHAPES, *wl.C3_SHAPES, wl.C5_SHAPES[0], *wl.c4_shapes()[::5]], ids=lambda s: "x".join(map(str, s)))
+def test_column_major_b_with_the_plans_tuned_for_that_layout(shape):
+    """B stored N x K (the paper's TN layout, Section 3) at the benchmark's sizes: the plan is the row of the table
+    tuned in that layout, the result is checked at sampled positions against the oracle (real inputs, tolerance)
+    and, on the exact-integer family of the shape, bit for bit."""
+    cfg = "C2" if shape in wl.C2_SHAPES else "C3" if shape in wl.C3_SHAPES else "C5" if shape in wl.C5_SHAPES else "C4"
+    a, b = {"C2": wl.c2_inputs, "C3": wl.c3_inputs, "C4": wl.c4_inputs, "C5": wl.c5_inputs}[cfg](shape)
+    c, before, after, desc = run_hgemm(a, np.ascontiguousarray(b.T), b_col_major=True, guard=1)
+    want = _tn_table().get(tuple(shape))
+    assert want is not None and desc.replace(",pad=1", "") == want, (shape, desc, want)
+    _check_sampled(a, b, c, 1500, f"TN {cfg} {shape} {desc}")
+    assert np.isnan(before).all() and np.isnan(after).all()
+    del a, b, c
+    name, ai, bi = wl.exact_family_for(shape, seed=17)
+    ci, _, _, _ = run_hgemm(ai, np.ascontiguousarray(bi.T), b_col_major=True)
+    ii, jj = wl.sample_positions(shape, 1500, seed=5)
+    ref = orc.hgemm_at(ai, bi, ii, jj)
+    sel = np.abs(ref.astype(np.float64)) <= 2048
+    assert sel.mean() > 0.5, name
+    assert np.array_equal(ci[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"TN {shape} {name} {desc}"
