@@ -12,7 +12,9 @@
  *
  * One plan per (M,N,K,layout): the paper's premise (Abstract, Section 5) is
  * that every shape wants its own kernel configuration; hgemm_plan() looks the
- * shape up in a table of measured choices and falls back to a fitted cost model.
+ * shape up in a table of measured choices (one table per layout of B; a shape
+ * tuned only with row-major B uses that row for column-major B too) and falls
+ * back to a fitted cost model.
  *
  * Threading: functions are thread-compatible (no global mutable state apart
  * from a read-only table and two per-device caches behind mutexes: whether a

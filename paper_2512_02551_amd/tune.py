@@ -33,7 +33,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE = os.path.join(_HERE, "csrc", "dispatch_table.inc")
 DEFAULT_LOG = os.path.join(_HERE, "csrc", "dispatch_tuning_log.jsonl")
-# B column-major (the paper's TN layout, Section 3): a table of its own, for the shapes tuned in that layout
+# B column-major (the TN layout of Section 2.2.2): a table of its own, for the shapes tuned in that layout
 TABLE_TN = os.path.join(_HERE, "csrc", "dispatch_table_tn.inc")
 DEFAULT_LOG_TN = os.path.join(_HERE, "csrc", "dispatch_tuning_log_tn.jsonl")
 

@@ -162,7 +162,7 @@ def _tn_table():
 
 @pytest.mark.parametrize("shape", [*wl.C2_SHAPES, *wl.C3_SHAPES, wl.C5_SHAPES[0], *wl.c4_shapes()[::5]], ids=lambda s: "x".join(map(str, s)))
 def test_column_major_b_with_the_plans_tuned_for_that_layout(shape):
-    """B stored N x K (the paper's TN layout, Section 3) at the benchmark's sizes: the plan is the row of the table
+    """B stored N x K (the TN layout of Section 2.2.2) at the benchmark's sizes: the plan is the row of the table
     tuned in that layout, the result is checked at sampled positions against the oracle (real inputs, tolerance)
     and, on the exact-integer family of the shape, bit for bit."""
     cfg = "C2" if shape in wl.C2_SHAPES else "C3" if shape in wl.C3_SHAPES else "C5" if shape in wl.C5_SHAPES else "C4"
