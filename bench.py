@@ -175,10 +175,14 @@ def paper_grid(args):
         b = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).half()
         c = torch.empty((M, N), device="cuda", dtype=torch.float16)
         c_lib = torch.empty_like(c)
+        tn = args.layout == "tn"
+        if tn:                                    # the same matrix stored N x K (column-major B, Section 2.2.2)
+            b = b.t().contiguous()
+        b_lib = b.t() if tn else b                # torch.matmul sees the strides and dispatches the library's TN kernel
         flop = 2.0 * M * N * K
         steps = max(2, min(args.steps, int(2e12 / flop) + 2))          # a few milliseconds of work per measurement
         warm = max(1, min(args.warmup, steps))
-        plan = hg.Plan(M, N, K)
+        plan = hg.Plan(M, N, K, hg.Layouts.make(b_col_major=True) if tn else None)
 
         def ours(n):
             for _ in range(n):
@@ -186,7 +190,7 @@ def paper_grid(args):
 
         def lib(n):
             for _ in range(n):
-                torch.matmul(a, b, out=c_lib)
+                torch.matmul(a, b_lib, out=c_lib)
 
         t = {}
         for name, fn in (("ours", ours), ("lib", lib)):
@@ -233,7 +237,7 @@ def paper_grid(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16 inputs/outputs, f32 accumulate", "data": "synthetic",
         "config": {"workload": "the paper's grid: 1000 triples over {64,...,16384}^3, uniform[-1,1], offline mode",
-                   "layout": "NN row-major", "cache": "warm",
+                   "layout": "TN (B column-major)" if args.layout == "tn" else "NN row-major", "cache": "warm",
                    "timing": ("best of three replays of a graph of back-to-back calls per shape (library too)" if args.graph else
                               "best of three batches of back-to-back calls per shape")},
         "library_context": {

@@ -53,6 +53,7 @@ struct Spec {
     int fr = 0;     // 1 = split-K with the reduction fused into the kernel (last-arriving workgroup sums in split order)
     int ps = 0;     // 1 = persistent: one workgroup per compute unit walks the tiles without draining its copy pipeline
     int ac = 32;    // accumulator width: 32 = fp32 over all of K; 16 = rounded to fp16 after every 16 products
+    int mi = 32;    // matrix-core output block: 32 = v_mfma_f32_32x32x16_f16, 16 = v_mfma_f32_16x16x32_f16
 };
 
 static std::string spec_to_string(const Spec& s)
@@ -69,6 +70,7 @@ static std::string spec_to_string(const Spec& s)
     if (s.fr) strncat(buf, ",fr=1", sizeof buf - strlen(buf) - 1);
     if (s.ps) strncat(buf, ",ps=1", sizeof buf - strlen(buf) - 1);
     if (s.ac == 16) strncat(buf, ",ac=16", sizeof buf - strlen(buf) - 1);
+    if (s.mi == 16) strncat(buf, ",mi=16", sizeof buf - strlen(buf) - 1);
     return buf;
 }
 
@@ -112,6 +114,7 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "fr") sp.fr = (int)v;
         else if (key == "ps") sp.ps = (int)v;
         else if (key == "ac") sp.ac = (int)v;
+        else if (key == "mi") sp.mi = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
@@ -119,6 +122,7 @@ static bool parse_spec(const char* text, Spec* out)
         return false;
     // the 16-bit accumulator is a running sum over all of K in k order: one tile per workgroup, no splitting of K
     if ((sp.ac != 32 && sp.ac != 16) || (sp.ac == 16 && (sp.fam != FAM_MFMA || sp.sk > 1 || sp.sm || sp.ps || sp.fr))) return false;
+    if (sp.mi != 32 && sp.mi != 16) return false;
     *out = sp;
     return true;
 }
@@ -126,7 +130,7 @@ static bool parse_spec(const char* text, Spec* out)
 static const MfmaEntry* find_entry(const Spec& s)
 {
     for (const MfmaEntry& e : registry())
-        if (e.bm == s.bm && e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.st == s.st && e.pf == s.pf) return &e;
+        if (e.bm == s.bm && e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.st == s.st && e.pf == s.pf && e.mi == s.mi) return &e;
     return nullptr;
 }
 
@@ -449,7 +453,7 @@ bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out, bool b_row_major =
         }
     }
     for (const MfmaEntry& e : registry()) {
-        if (e.deep) continue;                        // the cost model was not fitted to deep-staged kernels: the tuner's business
+        if (e.deep || e.mi != 32) continue;          // the cost model was not fitted to these kernels: the tuner's business
         if (!tile_fits_problem(e, M, N)) continue;
         const int64_t t = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
         const int64_t ktiles = (K + e.bk - 1) / e.bk;
@@ -559,8 +563,9 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     if (s.tb && p->lay.b != HGEMM_ROW_MAJOR) return HGEMM_ERR_UNSUPPORTED;
     p->tn_kernel = s.tb || p->lay.b == HGEMM_COL_MAJOR;
     p->entry = e;
-    // deep-staged configurations exist for one full-K tile per workgroup only
+    // deep-staged configurations exist for one full-K tile per workgroup only; the 16-bit accumulator for 32-wide blocks only
     if (e->deep && (s.sk > 1 || s.sm || s.ps || s.fr || s.ac == 16)) return HGEMM_ERR_UNSUPPORTED;
+    if (s.ac == 16 && !e->acc16) return HGEMM_ERR_UNSUPPORTED;
     // dynamic LDS beyond 64 KiB has to be requested per kernel function
     {
         void (*const kernels[])(GemmArgs) = {e->plain, e->splitk, e->plain_tn, e->splitk_tn, e->streamk, e->streamk_tn, e->splitk_fused,
@@ -987,7 +992,7 @@ const char* hgemm_spec_help(void)
             "    K slab each and stream it in steps of 64 rows (loads one step ahead, transposed through LDS, 16x16x32\n"
             "    matrix-core instructions with M on a 16-wide side); slabs are summed in slab order by the split-K\n"
             "    reduction launch or, with fr = 1, inside the kernel by the workgroup that arrives last\n"
-            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16]\n"
+            "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16][,mi=16]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
             "    sk = split-K factor (fp32 partials + ordered reduction), gm = tile-order group height (0 = row-major),\n"
@@ -1005,7 +1010,7 @@ const char* hgemm_spec_help(void)
             "            zero-padded packed copies held in the plan's workspace (decided by hgemm_plan from the shape)\n"
             "    compiled (bm,bn,bk,wm,wn,st,pf):";
         for (const MfmaEntry& e : registry()) {
-            if (e.deep) continue;
+            if (e.deep || e.mi != 32) continue;
             char b[64];
             snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
             t += b;
@@ -1015,7 +1020,17 @@ const char* hgemm_spec_help(void)
              "    32 k each keep st - 1 K-tiles of copies in flight); one full-K tile per workgroup only: sk = 1, no sm, ps, fr, ac\n"
              "    deep (bm,bn,bk,wm,wn,st,pf):";
         for (const MfmaEntry& e : registry()) {
-            if (!e.deep) continue;
+            if (!e.deep || e.mi != 32) continue;
+            char b[64];
+            snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
+            t += b;
+        }
+        t += "\n"
+             "    mi = 16: v_mfma_f32_16x16x32_f16 instead of v_mfma_f32_32x32x16_f16 (a k-step is then 32 k); one full-K tile per\n"
+             "    workgroup only, like the deep-staged ones\n"
+             "    mi16 (bm,bn,bk,wm,wn,st,pf):";
+        for (const MfmaEntry& e : registry()) {
+            if (e.mi != 16) continue;
             char b[64];
             snprintf(b, sizeof b, " (%d,%d,%d,%d,%d,%d,%d)", e.bm, e.bn, e.bk, e.wm, e.wn, e.st, e.pf);
             t += b;
@@ -1058,7 +1073,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                 for (int gm : {8, 0, 4, 16}) {
                     if (gm != 8 && (t < 2 * CUS)) continue;
                     Spec s;
-                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = 1; s.gm = gm;
+                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.mi = e.mi; s.sk = 1; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
                 }
@@ -1067,7 +1082,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
             const std::vector<int> sks = split_candidates(t, ktiles);
             if (t % CUS != 0 && ktiles >= 4 && e.bm >= 64 && e.bn >= 64) {
                 Spec s;
-                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = 1; s.gm = 8; s.sm = 1;
+                s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.mi = e.mi; s.sk = 1; s.gm = 8; s.sm = 1;
                 out += spec_to_string(s);
                 out += "\n";
             }
@@ -1075,7 +1090,7 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                 for (int gm : {8, 0, 4, 16}) {
                     if (gm != 8 && (t < 2 * CUS)) continue;      // order matters only when tiles outnumber CUs
                     Spec s;
-                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.sk = sk; s.gm = gm;
+                    s.fam = FAM_MFMA; s.bm = e.bm; s.bn = e.bn; s.bk = e.bk; s.wm = e.wm; s.wn = e.wn; s.st = e.st; s.pf = e.pf; s.mi = e.mi; s.sk = sk; s.gm = gm;
                     out += spec_to_string(s);
                     out += "\n";
                     if (sk == 1 && gm == 8 && e.persist && t > CUS && ktiles >= e.st) {      // the same tiles walked by persistent workgroups

@@ -19,7 +19,7 @@ template <class C> struct MaybeEntry<HGEMM_CHUNK, C> {
 
 void HGEMM_PASTE(register_chunk_, HGEMM_CHUNK)(std::vector<MfmaEntry>& out)
 {
-#define HGEMM_CFG(chunk, bm, bn, bk, wm, wn, st, pf) MaybeEntry<chunk, MfmaCfg<bm, bn, bk, wm, wn, st, pf>>::add(out);
+#define HGEMM_CFG(chunk, bm, bn, bk, wm, wn, st, ...) MaybeEntry<chunk, MfmaCfg<bm, bn, bk, wm, wn, st, __VA_ARGS__>>::add(out);
 #include "hgemm_configs.inc"
 }
 

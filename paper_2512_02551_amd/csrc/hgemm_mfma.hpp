@@ -245,15 +245,22 @@ __host__ __device__ inline void tile_coords(unsigned wg, const GemmArgs& g, unsi
 
 // PF = register prefetch distance in k-steps (Sections 5.3.1 and 5.3.2: PF = 1 is the
 // double-buffered ping-pong, PF = 3 the multi-step prefetch with four fragment sets).
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int PF_ = 1>
+// MI = side of the matrix-core instruction's output block: 32 (v_mfma_f32_32x32x16_f16, a k-step is 16 k) or
+// 16 (v_mfma_f32_16x16x32_f16, a k-step is 32 k).  Per flop the 16-wide instruction moves half as many
+// accumulator registers and twice as many operand registers, 20 % fewer in sum; the fragments come out of LDS
+// with the same reads either way (a 16-row fragment is 16 rows x 64 bytes instead of 32 rows x 32 bytes).
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int PF_ = 1, int MI_ = 32>
 struct MfmaCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
     static constexpr int PF = PF_, NSLOT = PF_ + 1;
     static constexpr int NWAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = 64 * NWAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;       // wave tile
-    static constexpr int TM = WTM / 32, TN = WTN / 32;                 // 32x32 MFMA tiles per wave
-    static constexpr int KS = BK / 16;                                 // k-steps per K-tile
+    static constexpr int MI = MI_;
+    static constexpr int KSTEP = MI == 32 ? 16 : 32;                   // k per matrix-core instruction
+    static constexpr int ACC = MI * MI / 64;                           // accumulator registers per output block
+    static constexpr int TM = WTM / MI, TN = WTN / MI;                 // MI x MI output blocks per wave
+    static constexpr int KS = BK / KSTEP;                              // k-steps per K-tile
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -271,8 +278,10 @@ struct MfmaCfg {
     // source offset per load instead of one offset plus a stride.
     static constexpr bool B_RAGGED = 64 % B_CPR != 0;
     // persistent mode stages the epilogue in the one buffer the last K-tile has just vacated
-    static constexpr bool CAN_PERSIST = NWAVES * 32 * (WTN * 2 + 8) <= STAGE_BYTES;
+    static constexpr bool CAN_PERSIST = NWAVES * MI_ * (WTN * 2 + 8) <= STAGE_BYTES;
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
+    static_assert(MI == 32 || MI == 16, "MI");
+    static_assert(BK % KSTEP == 0, "a K-tile holds whole k-steps");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     // Deep staging: a prefetch distance longer than a K-tile.  BK = 32 (two k-steps per K-tile) with PF = 3: the
     // fragment reads run three k-steps, i.e. up to two K-tiles, ahead of the matrix cores, the four fragment
@@ -355,6 +364,10 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     constexpr bool ACC16 = MODE == MODE_ACC16;
     constexpr bool DEEP = C::DEEP;
     static_assert(!DEEP || MODE == MODE_PLAIN, "deep-staged configurations run one full-K tile per workgroup");
+    constexpr int MI = C::MI;
+    static_assert(MI == 32 || !ACC16, "the 16-bit accumulator rounds after every 16 products: 32 x 32 x 16 instructions only");
+    constexpr int LG = MI == 32 ? 5 : 4;           // lane / MI = the lane's k-chunk within a k-step
+    constexpr int CPK = C::KSTEP / 8;               // 16-byte chunks (8 k) per k-step
     static_assert(!PERSIST || C::CAN_PERSIST, "epilogue staging must fit in one stage");
 
     // All arguments the set-up reads are pulled into scalar registers here, in one batch of loads:
@@ -502,21 +515,22 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 
     // ---- LDS -> register addressing ----------------------------------------
     // A fragment (fed as the MFMA "B" operand): lane holds A[m = l%32][8 consecutive k of half l/32]
-    const int fa_row = wm * C::WTM + (lane & 31);                         // + tm*32
+    const int fa_row = wm * C::WTM + (lane & (MI - 1));                   // + tm*MI
     const int fa_swz = swz_a<C>(fa_row);
     const int fa_base = fa_row * (C::BK * 2);
     // B fragment (fed as the MFMA "A" operand) through two transposing reads per 8 k-values
-    const int fb_krow = 8 * (lane >> 5) + ((lane & 15) >> 2);             // + 16*ks + 4*h
+    const int fb_krow = 8 * (lane >> LG) + ((lane & 15) >> 2);            // + KSTEP*ks + 4*h
     const int fb_swz = swz_b<C>(fb_krow);                                 // adding 16*ks + 4*h changes neither k&3 nor bit 1 of k
-    const int fb_ncol = wn * C::WTN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // + tn*32
+    const int fb_ncol = wn * C::WTN + (MI == 32 ? 16 * ((lane >> 4) & 1) : 0) + 4 * (lane & 3);   // + tn*MI
     // TN: B fragment read like an A fragment from the BN x BK tile
-    const int ft_row = wn * C::WTN + (lane & 31);                         // + tn*32
+    const int ft_row = wn * C::WTN + (lane & (MI - 1));                   // + tn*MI
     const int ft_swz = swz_a<C>(ft_row);
     const int ft_base = ft_row * (C::BK * 2);
 
     half8 fa[C::NSLOT][C::TM];
     half8 fb[C::NSLOT][C::TN];
-    float16v acc[C::TM][C::TN];       // zeroed at the start of every tile
+    typedef typename std::conditional<MI == 32, float16v, float4v>::type acc_t;
+    acc_t acc[C::TM][C::TN];          // zeroed at the start of every tile
 
     // Fragment read number r of a k-step: r < TM reads A fragment r, the rest read B fragment r-TM.
     constexpr int NREADS = C::TM + C::TN;
@@ -525,20 +539,20 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         const char* sA = lds + buf * C::STAGE_BYTES;
         const char* sB = sA + C::A_BYTES;
         if (r < C::TM) {
-            const int chunk = (2 * ks + (lane >> 5)) ^ fa_swz;
-            fa[slot][r] = *(const half8*)(sA + fa_base + r * 32 * (C::BK * 2) + chunk * 16);
+            const int chunk = (CPK * ks + (lane >> LG)) ^ fa_swz;
+            fa[slot][r] = *(const half8*)(sA + fa_base + r * MI * (C::BK * 2) + chunk * 16);
         } else if (TN) {
             const int tn = r - C::TM;
-            const int chunk = (2 * ks + (lane >> 5)) ^ ft_swz;
-            fb[slot][tn] = *(const half8*)(sB + ft_base + tn * 32 * (C::BK * 2) + chunk * 16);
+            const int chunk = (CPK * ks + (lane >> LG)) ^ ft_swz;
+            fb[slot][tn] = *(const half8*)(sB + ft_base + tn * MI * (C::BK * 2) + chunk * 16);
         } else {
             const int tn = r - C::TM;
-            const int n = fb_ncol + tn * 32;
+            const int n = fb_ncol + tn * MI;
             const int off = ((n >> 3) ^ fb_swz) * 16 + (n & 7) * 2;
             short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (16 * ks + fb_krow) * (C::BN * 2) + off));
+                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (C::KSTEP * ks + fb_krow) * (C::BN * 2) + off));
             short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (16 * ks + 4 + fb_krow) * (C::BN * 2) + off));
+                (__attribute__((address_space(3))) short4v*)HGEMM_LDS(sB + (C::KSTEP * ks + 4 + fb_krow) * (C::BN * 2) + off));
             union { struct { short4v lo, hi; } s; half8 h; } u;
             u.s.lo = lo;
             u.s.hi = hi;
@@ -551,7 +565,8 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     };
     auto mma_one = [&](int slot, int i) {
         const int tm = i / C::TN, tn = i % C::TN;
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
+        if constexpr (MI == 32) acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
+        else acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
     };
     // 16-bit accumulator: the running sums are fp16 values between matrix-core instructions (round to nearest
     // even, overflow to infinity).  Every accumulator block takes exactly one instruction per k-step, so the
@@ -562,7 +577,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[tm][tn][e] = (float)(_Float16)acc[tm][tn][e];
+                for (int e = 0; e < C::ACC; ++e) acc[tm][tn][e] = (float)(_Float16)acc[tm][tn][e];
     };
 
     // One k-step with a pinned instruction order: matrix-core instruction i is followed by its
@@ -645,7 +660,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 #pragma unroll
         for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < C::ACC; ++v) acc[i][j][v] = 0.f;
     if constexpr (DEEP) {
         // Deep-staged main loop.  The reads lead the matrix cores by three k-steps; "the read tile" is the K-tile
         // the reads are in.  When the reads move on to the next K-tile: that tile must have landed (all copies but
@@ -726,9 +741,11 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     }
 
     // ---- epilogue ------------------------------------------------------------
-    // acc[tm][tn][v]: row m = m0 + wm*WTM + tm*32 + l%32, columns n = n0 + wn*WTN + tn*32 + 8*(v/4) + 4*(l/32) + v%4
-    const int row_t = wm * C::WTM + (lane & 31);           // tile-local
-    const int col_t = wn * C::WTN + 4 * (lane >> 5);
+    // acc[tm][tn][v]: row m = m0 + wm*WTM + tm*MI + l%MI, columns n = n0 + wn*WTN + tn*MI + 8*(v/4) + 4*(l/MI) + v%4
+    // (MI = 16: v < 4, one group of 4 consecutive columns per block)
+    const int row_t = wm * C::WTM + (lane & (MI - 1));     // tile-local
+    const int col_t = wn * C::WTN + 4 * (lane >> LG);
+    constexpr int VG = C::ACC / 4;                         // groups of 4 consecutive columns a lane holds per output block
     if (!to_partial) {
         // fp32 -> fp16 (round to nearest even), then through LDS so that a lane stores 16 contiguous
         // bytes and a wave whole row segments (Section 5.3.3: registers -> shared -> global with wide
@@ -737,27 +754,28 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         constexpr int ROWB = C::WTN * 2 + 8;      // +8 bytes: the 32 rows a half-wave writes hit 32 different banks pairs
         constexpr int CPR = C::WTN / 8;           // 16-byte chunks per slab row
         // persistent mode: only the buffer of the last K-tile is free (the others hold the next tile's first K-tiles)
-        char* stage = lds + (PERSIST ? buf * C::STAGE_BYTES : 0) + wave * (32 * ROWB);
-        static_assert(C::NWAVES * 32 * ROWB <= C::LDS_BYTES, "epilogue staging must fit in the operand buffers");
+        char* stage = lds + (PERSIST ? buf * C::STAGE_BYTES : 0) + wave * (MI * ROWB);
+        static_assert(C::NWAVES * MI * ROWB <= C::LDS_BYTES, "epilogue staging must fit in the operand buffers");
+        static_assert(MI * CPR >= 64, "a slab holds at least one 16-byte chunk per lane");
 #pragma unroll
         for (int tm = 0; tm < C::TM; ++tm) {
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn) {
 #pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
+                for (int vg = 0; vg < VG; ++vg) {
                     half4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[tm][tn][vg * 4 + e];
-                    *(half4*)(stage + (lane & 31) * ROWB + (tn * 32 + vg * 8 + 4 * (lane >> 5)) * 2) = o;
+                    *(half4*)(stage + (lane & (MI - 1)) * ROWB + (tn * MI + vg * 8 + 4 * (lane >> LG)) * 2) = o;
                 }
             }
 #pragma unroll
-            for (int j = 0; j < (32 * CPR) / 64; ++j) {
+            for (int j = 0; j < (MI * CPR) / 64; ++j) {
                 const int idx = j * 64 + lane;
                 const int r = idx / CPR, ch = idx % CPR;
                 const half4 lo = *(const half4*)(stage + r * ROWB + ch * 16);
                 const half4 hi = *(const half4*)(stage + r * ROWB + ch * 16 + 8);
-                const int m = m0 + wm * C::WTM + tm * 32 + r;
+                const int m = m0 + wm * C::WTM + tm * MI + r;
                 const int n = n0 + wn * C::WTN + ch * 8;
                 if (m < g.M && n < g.N) {
                     half8 v;
@@ -774,17 +792,17 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             sk_slot = g.partial + ((size_t)2 * ((int)blockIdx.x - g.dp_tiles) + (first_segment ? 0 : 1)) * (size_t)(C::BM * C::BN);
 #pragma unroll
         for (int tm = 0; tm < C::TM; ++tm) {
-            const int m = m0 + row_t + tm * 32;
+            const int m = m0 + row_t + tm * MI;
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn) {
 #pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    const int n = n0 + col_t + tn * 32 + vg * 8;
+                for (int vg = 0; vg < VG; ++vg) {
+                    const int n = n0 + col_t + tn * MI + vg * 8;
                     float4v o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = acc[tm][tn][vg * 4 + e];
                     if (STREAMK) {
-                        *(float4v*)(sk_slot + (row_t + tm * 32) * C::BN + col_t + tn * 32 + vg * 8) = o;
+                        *(float4v*)(sk_slot + (row_t + tm * MI) * C::BN + col_t + tn * MI + vg * 8) = o;
                     } else if (m < g.M && n < g.N) {
                         float* dst = g.partial + ((size_t)split * g.M + m) * g.N + n;
                         if (FUSED) {

@@ -210,15 +210,29 @@ def test_persistent_mode_every_capable_spec_bit_exact():
         assert np.array_equal(p1.view(np.uint16), p2.view(np.uint16)) and np.array_equal(p1.view(np.uint16), plain.view(np.uint16)), desc
 
 
-def deep_specs(gm=8):
+def _listed_specs(gm=8):
+    """(spec, deep) for the configurations spec_help lists on lines of their own: the deep-staged ones (prefetch distance
+    longer than a K-tile: one full-K tile per workgroup only) and those built on the 16 x 16 x 32 matrix-core instruction
+    (mi=16, a k-step is 32 k)."""
     out = []
     for line in hg.spec_help().splitlines():
-        if line.strip().startswith("deep (bm"):
+        head = line.strip()
+        if head.startswith("deep (bm") or head.startswith("mi16 (bm"):
+            mi16 = head.startswith("mi16")
             for tup in line.split(":")[1].split():
                 bm, bn, bk, wm, wn, st, pf = (int(x) for x in tup.strip("()").split(","))
-                out.append(f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},pf={pf},sk=1,gm={gm}")
-    assert out
+                spec = f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},pf={pf},sk=1,gm={gm}" + (",mi=16" if mi16 else "")
+                out.append((spec, pf > bk // (32 if mi16 else 16)))
+    assert any("mi=16" in s for s, _ in out) and any("mi=16" not in s for s, _ in out)
     return out
+
+
+def deep_specs(gm=8):
+    return [s for s, deep in _listed_specs(gm) if deep]
+
+
+def mi16_specs(gm=8):
+    return [s for s, deep in _listed_specs(gm) if not deep and "mi=16" in s]
 
 
 @pytest.mark.parametrize("shape", [(300, 264, 200), (257, 520, 328), (512, 512, 40), (260, 304, 8), (520, 264, 2056), (1030, 1544, 96)])
@@ -252,6 +266,27 @@ def test_deep_staged_specs_real_inputs_repeatable_and_refusals():
         for bad in (spec.replace("sk=1", "sk=2"), spec + ",sm=1", spec + ",ps=1", spec + ",ac=16", spec.replace("sk=1", "sk=2") + ",fr=1"):
             with pytest.raises(hg.HgemmError):
                 hg.Plan(*shape, None, bad)
+
+
+@pytest.mark.parametrize("shape", [(300, 264, 200), (257, 520, 328), (520, 776, 2056), (1030, 1544, 96)])
+def test_16_wide_matrix_core_blocks_bit_exact_in_every_mode_both_layouts(shape):
+    """v_mfma_f32_16x16x32_f16 configurations (mi=16): other fragment and accumulator layouts, the same result.  One
+    tile per workgroup, split-K (two launches and fused), stream-K and persistent mode, ragged M, N and K, both
+    layouts of B; the 16-bit accumulator is refused (its rounding step is the 16-product step of the 32-wide blocks)."""
+    name, a, b = wl.exact_family_for(shape, seed=73)
+    ref = orc.hgemm(a, b)
+    bt = np.ascontiguousarray(b.T)
+    specs = mi16_specs()
+    assert specs
+    for spec in specs:
+        for variant in (spec, spec.replace("sk=1", "sk=3"), spec.replace("sk=1", "sk=2") + ",fr=1", spec + ",sm=1", spec + ",ps=1"):
+            c, before, after, desc = run_hgemm(a, b, spec=variant, guard=2)
+            assert_bit_exact(c, ref, f"{shape} {name} {desc}")
+            assert np.isnan(before).all() and np.isnan(after).all(), desc
+            c, _, _, desc = run_hgemm(a, bt, spec=variant, b_col_major=True)
+            assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
+        with pytest.raises(hg.HgemmError):
+            hg.Plan(*shape, None, spec + ",ac=16")
 
 
 def test_server_mode_idle_gaps_between_calls():
