@@ -36,16 +36,18 @@ def test_committed_table_names_only_compiled_kernels_and_covers_the_workloads(ta
     rows = re.findall(r'\{(\d+), (\d+), (\d+), "([^"]*)"\}', text)
     compiled = set()
     for line in hg.spec_help().splitlines():
-        if "compiled" in line or line.strip().startswith("deep (bm"):      # the deep-staged configurations have a line of their own
+        head = line.strip()
+        # the deep-staged configurations and those on the 16 x 16 x 32 instruction have lines of their own
+        if "compiled" in line or head.startswith("deep (bm") or head.startswith("mi16 (bm"):
             for tup in line.split(":")[1].split():
-                compiled.add(tuple(int(x) for x in tup.strip("()").split(",")))
+                compiled.add(tuple(int(x) for x in tup.strip("()").split(",")) + (16 if head.startswith("mi16") else 32,))
     shapes = set()
     for m, n, k, spec in rows:
         if not spec:
             continue
         shapes.add((int(m), int(n), int(k)))
         kv = dict(re.findall(r"(\w+)=(\d+)", spec))
-        key = tuple(int(kv.get(x, 1 if x == "pf" else 0)) for x in ("bm", "bn", "bk", "wm", "wn", "st", "pf"))
+        key = tuple(int(kv.get(x, 1 if x == "pf" else 0)) for x in ("bm", "bn", "bk", "wm", "wn", "st", "pf")) + (int(kv.get("mi", 32)),)
         assert key in compiled, f"table row {m}x{n}x{k} names a kernel that is not compiled: {spec}"
         if table.endswith("_tn.inc"):          # column-major B: no transposing copy, and 64-byte K runs (bk = 32) never win
             assert "tb=1" not in spec
