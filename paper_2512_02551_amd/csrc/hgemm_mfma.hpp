@@ -39,6 +39,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 namespace hgemm {
 
@@ -353,6 +354,19 @@ template <int N> __device__ inline void wait_vmcnt()
 
 // TN = B stored column-major, i.e. as an N x K row-major array (Section 2.2.2): then B tiles are
 // staged and read exactly like A tiles (K contiguous), with no transposing read.
+// ic<V>{} passes a compile-time integer into a lambda; static_for<N>(f) calls f(ic<0>{}), ..., f(ic<N-1>{}).
+// The k-step lambdas take their fragment-set numbers this way, so that the fragment arrays are indexed by
+// constants in every instantiation, whatever order the optimiser inlines and unrolls in.
+template <int V> using ic = std::integral_constant<int, V>;
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(ic<I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <class C, int MODE, bool TN>
 __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 {
@@ -580,30 +594,44 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
                 for (int e = 0; e < C::ACC; ++e) acc[tm][tn][e] = (float)(_Float16)acc[tm][tn][e];
     };
 
+    using std::integral_constant;
     // One k-step with a pinned instruction order: matrix-core instruction i is followed by its
     // share of the side work (fragment reads for the k-step PF steps ahead, and after the barrier
     // of a tile the global->LDS copies of a later tile), so that the side work issues in the shadow
     // of the matrix cores instead of in a burst in front of them (the staggered prefetch of
     // Section 5.3.4, taken to instruction granularity).
     // Copies [dma_lo, dma_hi) of tile dma_kt go to buffer dma_buf.
-    auto kstep = [&](int slot, int rbuf, int rks, int rslot, bool do_reads, int dma_kt, int dma_buf, int dma_lo, int dma_hi) {
-        constexpr int NSIDE_MAX = NREADS + C::LOADS;
-        const int nreads = do_reads ? NREADS : 0;
-        const int nside = nreads + (dma_hi - dma_lo);
-#pragma unroll
-        for (int i = 0; i < NMMA; ++i) {
+    // Everything that selects a register or an instruction slot is a compile-time value (tags), so the fragment and
+    // accumulator arrays are indexed by constants in every instantiation, whatever the optimiser inlines or unrolls.
+    // (A k-step of more than 32 matrix-core instructions is issued in two halves: one lambda with all of them is too
+    // large for the inliner, and a lambda that stays a call reaches the buffer descriptors through memory.)
+    auto kstep_part = [&](auto i0_tag, auto i1_tag, auto slot_tag, int rbuf, int rks, auto rslot_tag, auto do_reads_tag, int dma_kt, int dma_buf,
+                          auto dma_lo_tag, auto dma_hi_tag) {
+        constexpr int i0 = decltype(i0_tag)::value, i1 = decltype(i1_tag)::value;
+        constexpr int slot = decltype(slot_tag)::value, rslot = decltype(rslot_tag)::value;
+        constexpr int dma_lo = decltype(dma_lo_tag)::value, dma_hi = decltype(dma_hi_tag)::value;
+        constexpr int nreads = decltype(do_reads_tag)::value ? NREADS : 0;
+        constexpr int nside = nreads + (dma_hi - dma_lo);
+        static_for<i1 - i0>([&](auto ii) {
+            constexpr int i = i0 + decltype(ii)::value;
             mma_one(slot, i);
             // side ops [lo, hi) go after MFMA i: spread nside ops evenly over the NMMA slots
-            const int lo = (i * nside) / NMMA, hi = ((i + 1) * nside) / NMMA;
-#pragma unroll
-            for (int t = 0; t < NSIDE_MAX; ++t) {
-                if (t >= lo && t < hi) {
-                    // fragment reads first (they are needed soonest), then the copies
-                    if (t < nreads) read_one(rbuf, rks, rslot, t);
-                    else dma_one(dma_kt, dma_buf, dma_lo + t - nreads);
-                }
-            }
+            constexpr int lo = (i * nside) / NMMA, hi = ((i + 1) * nside) / NMMA;
+            static_for<hi - lo>([&](auto tt) {
+                constexpr int t = lo + decltype(tt)::value;
+                // fragment reads first (they are needed soonest), then the copies
+                if constexpr (t < nreads) read_one(rbuf, rks, rslot, t);
+                else dma_one(dma_kt, dma_buf, dma_lo + t - nreads);
+            });
             __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    auto kstep = [&](auto slot, int rbuf, int rks, auto rslot, auto do_reads, int dma_kt, int dma_buf, auto dma_lo, auto dma_hi) {
+        if constexpr (NMMA > 32) {
+            kstep_part(ic<0>{}, ic<NMMA / 2>{}, slot, rbuf, rks, rslot, do_reads, dma_kt, dma_buf, dma_lo, dma_hi);
+            kstep_part(ic<NMMA / 2>{}, ic<NMMA>{}, slot, rbuf, rks, rslot, do_reads, dma_kt, dma_buf, dma_lo, dma_hi);
+        } else {
+            kstep_part(ic<0>{}, ic<NMMA>{}, slot, rbuf, rks, rslot, do_reads, dma_kt, dma_buf, dma_lo, dma_hi);
         }
     };
 
@@ -618,27 +646,26 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         constexpr int WAIT = decltype(wait_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool DMA = decltype(dma_tag)::value;
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bool after = ks >= C::KS - C::PF;            // this step runs behind the barrier
+        static_for<C::KS>([&](auto ks_tag) {
+            constexpr int ks = decltype(ks_tag)::value;
+            constexpr bool after = ks >= C::KS - C::PF;        // this step runs behind the barrier
             if (ks == C::KS - C::PF && HAS_NEXT) {
                 wait_vmcnt<WAIT>();
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
-            const int t = ks + C::PF;
-            const bool in_next = t >= C::KS;
-            const int j = ks - (C::KS - C::PF);                 // index among the post-barrier steps
-            const int dlo = (DMA && after) ? (j * C::LOADS) / C::PF : 0;
-            const int dhi = (DMA && after) ? ((j + 1) * C::LOADS) / C::PF : 0;
-            kstep(ks % C::NSLOT, in_next ? nbuf : buf, in_next ? t - C::KS : t, t % C::NSLOT, in_next ? HAS_NEXT : true,
-                  dma_kt, buf, dlo, dhi);
+            constexpr int t = ks + C::PF;
+            constexpr bool in_next = t >= C::KS;
+            constexpr int j = ks - (C::KS - C::PF);             // index among the post-barrier steps
+            constexpr int dlo = (DMA && after) ? (j * C::LOADS) / C::PF : 0;
+            constexpr int dhi = (DMA && after) ? ((j + 1) * C::LOADS) / C::PF : 0;
+            kstep(ic<ks % C::NSLOT>{}, in_next ? nbuf : buf, in_next ? t - C::KS : t, ic<t % C::NSLOT>{},
+                  std::bool_constant<(in_next ? HAS_NEXT : true)>{}, dma_kt, buf, ic<dlo>{}, ic<dhi>{});
             if (ACC16) {
                 round_accumulators();
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        });
     };
-    using std::integral_constant;
 
     // ---- main loop ----------------------------------------------------------
     int buf = 0;                      // LDS buffer of the K-tile being multiplied
@@ -695,12 +722,12 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         // One pass = two K-tiles = four k-steps; k-step u multiplies fragment set u and reads the k-step three
         // ahead into set (u + 3) % 4.  A refill is issued in two halves: behind the barrier, and in the k-step after.
         for (int t2 = 0; t2 < KT2; t2 += 2) {
-            kstep(0, rb, 1, 3, true, dkt, dbuf, L / 2, L);
+            kstep(ic<0>{}, rb, 1, ic<3>{}, std::true_type{}, dkt, dbuf, ic<L / 2>{}, ic<L>{});
             enter_next_tile();
-            kstep(1, rb, 0, 0, true, dkt, dbuf, 0, L / 2);
-            kstep(2, rb, 1, 1, true, dkt, dbuf, L / 2, L);
+            kstep(ic<1>{}, rb, 0, ic<0>{}, std::true_type{}, dkt, dbuf, ic<0>{}, ic<L / 2>{});
+            kstep(ic<2>{}, rb, 1, ic<1>{}, std::true_type{}, dkt, dbuf, ic<L / 2>{}, ic<L>{});
             enter_next_tile();
-            kstep(3, rb, 0, 2, true, dkt, dbuf, 0, L / 2);
+            kstep(ic<3>{}, rb, 0, ic<2>{}, std::true_type{}, dkt, dbuf, ic<0>{}, ic<L / 2>{});
         }
         wait_vmcnt<0>();                     // copies still in flight would land in the epilogue's staging area
     } else if (KT > 0) {
