@@ -305,12 +305,19 @@ template <class C> __device__ inline int swz_a(int row) { return (row / C::A_RP)
 // XOR applied to the chunk index of a B row (rows of BN halves): the four rows
 // k..k+3 one transposing read touches must land in four different 64-byte
 // quarters of the 256-byte bank window.
+// With the 16 x 16 x 32 instruction the first 32 lanes of a transposing read hold two groups of 16 lanes that
+// read the same columns at rows k and k + 8 (with 32 x 32 x 16 the two groups read different columns): bit 3 of k
+// then moves the row by another 32 bytes, and the two groups meet in different banks.  Only where one offset per
+// lane still serves all of a lane's copies, i.e. where the rows of a lane's copies differ by multiples of 16
+// (or every copy has an offset of its own, B_RAGGED).
 template <class C> __device__ inline int swz_b(int k)
 {
     constexpr int PITCH = (C::BN * 2) % 256;      // where consecutive rows start inside the 256-byte bank window
-    if (PITCH == 0) return (k & 3) << 2;          // BN = 128, 256, 512: all four rows would start at the same place
-    if (PITCH == 128) return ((k >> 1) & 1) << 2; // BN = 64, 192: rows k and k+1 already differ, k and k+2 do not
-    return 0;                                     // BN = 96, 160: the four rows start in four different quarters
+    constexpr bool BIT3 = C::MI == 16 && (PITCH == 0 || PITCH == 128) && (C::B_RAGGED || (C::NWAVES * C::B_RPI) % 16 == 0);
+    const int hi = BIT3 ? ((k >> 3) & 1) << 1 : 0;
+    if (PITCH == 0) return ((k & 3) << 2) ^ hi;          // BN = 128, 256, 512: all four rows would start at the same place
+    if (PITCH == 128) return (((k >> 1) & 1) << 2) ^ hi; // BN = 64, 192: rows k and k+1 already differ, k and k+2 do not
+    return 0;                                            // BN = 96, 160: the four rows start in four different quarters
 }
 
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -534,7 +541,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
     const int fa_base = fa_row * (C::BK * 2);
     // B fragment (fed as the MFMA "A" operand) through two transposing reads per 8 k-values
     const int fb_krow = 8 * (lane >> LG) + ((lane & 15) >> 2);            // + KSTEP*ks + 4*h
-    const int fb_swz = swz_b<C>(fb_krow);                                 // adding 16*ks + 4*h changes neither k&3 nor bit 1 of k
+    const int fb_swz = swz_b<C>(fb_krow);                                 // adding KSTEP*ks + 4*h changes none of k&3, bit 1 and bit 3 of k
     const int fb_ncol = wn * C::WTN + (MI == 32 ? 16 * ((lane >> 4) & 1) : 0) + 4 * (lane & 3);   // + tn*MI
     // TN: B fragment read like an A fragment from the BN x BK tile
     const int ft_row = wn * C::WTN + (lane & (MI - 1));                   // + tn*MI
