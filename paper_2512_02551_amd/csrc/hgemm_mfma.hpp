@@ -288,8 +288,10 @@ struct MfmaCfg {
     // fragment reads run three k-steps, i.e. up to two K-tiles, ahead of the matrix cores, the four fragment
     // sets cycle once per two K-tiles, and five 32 KiB stages keep four K-tiles of copies in flight -- twice the
     // lead of two 64 KiB stages in the same LDS.  One tile per workgroup only (no split-K, stream-K, persistence).
-    static constexpr bool DEEP = PF > KS;
-    static_assert(DEEP ? (KS == 2 && PF == 3 && STAGES >= 4)
+    // With the 16-wide instruction a K-tile of 32 is a single k-step (KS = 1, PF = 1): the same uniform loop with one
+    // k-step per K-tile, two fragment sets, and the reads one K-tile ahead.
+    static constexpr bool DEEP = PF > KS || KS == 1;
+    static_assert(DEEP ? ((KS == 2 && PF == 3 && STAGES >= 4) || (KS == 1 && PF == 1 && STAGES >= 3))
                        : (KS % NSLOT == 0 && PF >= 1), "the k-steps must cycle through the fragment sets a whole number of times");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into wave loads");
     static_assert(BN >= 64 && BN <= 512, "BN");
@@ -584,8 +586,13 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
 #pragma unroll
         for (int r = 0; r < NREADS; ++r) read_one(buf, ks, slot, r);
     };
+    // Order of the output blocks within a k-step.  With prefetch distance 1 the fragments of this k-step were read
+    // during the previous one, A fragments first and B fragments last: walking the blocks column by column uses the
+    // B fragment that arrived last, last (its read is then most of a k-step old), instead of after a handful of
+    // instructions -- which is what one wave per SIMD needs, having no second wave to cover a late fragment.  With
+    // longer prefetch distances every fragment is old enough and the order is row by row.
     auto mma_one = [&](int slot, int i) {
-        const int tm = i / C::TN, tn = i % C::TN;
+        const int tm = C::PF == 1 ? i % C::TM : i / C::TN, tn = C::PF == 1 ? i / C::TM : i % C::TN;
         if constexpr (MI == 32) acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
         else acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[slot][tn], fa[slot][tm], acc[tm][tn], 0, 0, 0);
     };
@@ -719,6 +726,19 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
         wait_vmcnt<(S - 1) * L>();
         asm volatile("s_barrier" ::: "memory");
         read_frags(0, 0, 0);
+      if constexpr (C::KS == 1) {
+        // One k-step per K-tile: a pass multiplies the fragments of K-tile t (set t % 2), reads those of K-tile t + 1
+        // into the other set and refills the buffer K-tile t has left with K-tile t + STAGES.
+        __builtin_amdgcn_sched_barrier(0);
+        const int KT2 = (KT + 1) & ~1;
+        for (int t2 = 0; t2 < KT2; t2 += 2) {
+            enter_next_tile();
+            kstep(ic<0>{}, rb, 0, ic<1>{}, std::true_type{}, dkt, dbuf, ic<0>{}, ic<L>{});
+            enter_next_tile();
+            kstep(ic<1>{}, rb, 0, ic<0>{}, std::true_type{}, dkt, dbuf, ic<0>{}, ic<L>{});
+        }
+        wait_vmcnt<0>();                     // copies still in flight would land in the epilogue's staging area
+      } else {
         read_frags(0, 1, 1);
         enter_next_tile();
 #pragma unroll
@@ -737,6 +757,7 @@ __global__ __launch_bounds__(C::THREADS) void mfma_gemm_kernel(GemmArgs g)
             kstep(ic<3>{}, rb, 0, ic<2>{}, std::true_type{}, dkt, dbuf, ic<0>{}, ic<L / 2>{});
         }
         wait_vmcnt<0>();                     // copies still in flight would land in the epilogue's staging area
+      }
     } else if (KT > 0) {
         constexpr int STEADY = (C::STAGES - 2) * C::LOADS;
         int kt = 0;

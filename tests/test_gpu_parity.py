@@ -222,7 +222,8 @@ def _listed_specs(gm=8):
             for tup in line.split(":")[1].split():
                 bm, bn, bk, wm, wn, st, pf = (int(x) for x in tup.strip("()").split(","))
                 spec = f"mfma,bm={bm},bn={bn},bk={bk},wm={wm},wn={wn},st={st},pf={pf},sk=1,gm={gm}" + (",mi=16" if mi16 else "")
-                out.append((spec, pf > bk // (32 if mi16 else 16)))
+                ks = bk // (32 if mi16 else 16)                 # k-steps per K-tile
+                out.append((spec, pf > ks or ks == 1))
     assert any("mi=16" in s for s, _ in out) and any("mi=16" not in s for s, _ in out)
     return out
 
