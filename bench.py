@@ -51,20 +51,20 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # roofline.traffic with roofline.traffic_source saying so.
 PROFILED_TRAFFIC_BYTES = {
     (1024, 1024, 1024): (6188.0 * 2.0 + 2048.0) * 1024,
-    (2048, 2048, 2048): (24631.0 * 2.0 + 8192.0) * 1024,
-    (4096, 4096, 4096): (147520.5 * 2.0 + 32768.0) * 1024,
-    (8192, 8192, 8192): (786498.9 * 2.0 + 131072.0) * 1024,
-    (16384, 16384, 8192): (3153615.4 * 2.0 + 528384.0) * 1024,
-    (16384, 16384, 16384): (6949619.0 * 2.0 + 528384.0) * 1024,
+    (2048, 2048, 2048): (24633.0 * 2.0 + 8192.0) * 1024,
+    (4096, 4096, 4096): (147517.0 * 2.0 + 32768.0) * 1024,
+    (8192, 8192, 8192): (786489.6 * 2.0 + 131072.0) * 1024,
+    (16384, 16384, 8192): (3152703.9 * 2.0 + 532480.1) * 1024,
+    (16384, 16384, 16384): (6937502.9 * 2.0 + 532480.0) * 1024,
     # cold skinny shapes (the HBM roofline's candidates); sums over the kernels of one call
     (1, 4096, 4096): (16498.6 * 2.0 + 146.0) * 1024,
-    (16, 4096, 4096): (17724.5 * 2.0 + 1664.0) * 1024,
-    (1, 11008, 4096): (44214.4 * 2.0 + 372.2) * 1024,
-    (16, 11008, 4096): (91988.1 * 2.0 + 6192.0) * 1024,
+    (16, 4096, 4096): (17723.5 * 2.0 + 1664.0) * 1024,
+    (1, 11008, 4096): (44214.7 * 2.0 + 372.2) * 1024,
+    (16, 11008, 4096): (45994.0 * 2.0 + 3096.0) * 1024,
     (1, 4096, 11008): (44201.6 * 2.0 + 146.0) * 1024,
-    (16, 4096, 11008): (91965.7 * 2.0 + 2304.0) * 1024,
-    (1, 14336, 4096): (57414.8 * 2.0 + 28.0) * 1024,
-    (16, 14336, 4096): (57894.8 * 2.0 + 448.0) * 1024,
+    (16, 4096, 11008): (45982.9 * 2.0 + 1152.0) * 1024,
+    (1, 14336, 4096): (57415.4 * 2.0 + 28.0) * 1024,
+    (16, 14336, 4096): (57895.3 * 2.0 + 448.0) * 1024,
 }
 
 
