@@ -36,7 +36,7 @@ static const std::vector<MfmaEntry>& registry()
     return r;
 }
 
-void (*skinny_kernel(int mb, bool fused))(GemmArgs);      // hgemm_skinny.hip
+void (*skinny_kernel(int mb, bool fused, int waves))(GemmArgs);      // hgemm_skinny.hip
 
 constexpr int64_t kSkinnyMaxM = 64;
 
@@ -54,7 +54,11 @@ struct Spec {
     int ps = 0;     // 1 = persistent: one workgroup per compute unit walks the tiles without draining its copy pipeline
     int ac = 32;    // accumulator width: 32 = fp32 over all of K; 16 = rounded to fp16 after every 16 products
     int mi = 32;    // matrix-core output block: 32 = v_mfma_f32_32x32x16_f16, 16 = v_mfma_f32_16x16x32_f16
+    int wv = 4;     // skinny family: waves per workgroup (4, 8 or 16), each taking 16 k-rows of a step
 };
+
+// k-rows a workgroup of the skinny family takes per step; K slabs are whole numbers of steps
+static int64_t skinny_step(const Spec& s) { return 16 * s.wv; }
 
 static std::string spec_to_string(const Spec& s)
 {
@@ -62,6 +66,7 @@ static std::string spec_to_string(const Spec& s)
     if (s.fam == FAM_GENERIC) return "generic";
     if (s.fam == FAM_SKINNY) {
         snprintf(buf, sizeof buf, "skinny,sk=%d%s", s.sk, s.fr ? ",fr=1" : "");
+        if (s.wv != 4) snprintf(buf + strlen(buf), sizeof buf - strlen(buf), ",wv=%d", s.wv);
         return buf;
     }
     snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,pf=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
@@ -115,6 +120,7 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "ps") sp.ps = (int)v;
         else if (key == "ac") sp.ac = (int)v;
         else if (key == "mi") sp.mi = (int)v;
+        else if (key == "wv") sp.wv = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
@@ -123,6 +129,7 @@ static bool parse_spec(const char* text, Spec* out)
     // the 16-bit accumulator is a running sum over all of K in k order: one tile per workgroup, no splitting of K
     if ((sp.ac != 32 && sp.ac != 16) || (sp.ac == 16 && (sp.fam != FAM_MFMA || sp.sk > 1 || sp.sm || sp.ps || sp.fr))) return false;
     if (sp.mi != 32 && sp.mi != 16) return false;
+    if ((sp.wv != 4 && sp.wv != 8 && sp.wv != 16) || (sp.wv != 4 && sp.fam != FAM_SKINNY)) return false;
     *out = sp;
     return true;
 }
@@ -419,10 +426,11 @@ double fused_delta_us(int64_t M, int64_t N, int64_t sk)
     return -0.8 + 1.6 * planes_mib;
 }
 
-// Slab counts worth considering for the skinny family (distinct after rounding to whole 64-row steps).
+// Slab counts worth considering for the skinny family (distinct after rounding to whole steps of a
+// four-wave workgroup, 64 rows).
 std::vector<int> skinny_split_candidates(int64_t N, int64_t K)
 {
-    const int64_t ksteps = (K + kSkinnyStep - 1) / kSkinnyStep, strips = (N + kSkinnyCols - 1) / kSkinnyCols;
+    const int64_t ksteps = (K + 63) / 64, strips = (N + kSkinnyCols - 1) / kSkinnyCols;
     std::vector<int> out;
     int64_t last = 0;
     for (int sk : {1, 2, 4, 8, 16, 32, 64, 128}) {
@@ -525,21 +533,22 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
         if (p->lay.b != HGEMM_ROW_MAJOR || !fast_path_ok(M, N, K, p->lay) || M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM)
             return HGEMM_ERR_UNSUPPORTED;
         const int mb = M <= 16 ? 1 : M <= 32 ? 2 : 4;
-        const int64_t ksteps = (K + kSkinnyStep - 1) / kSkinnyStep;
+        const int64_t step = skinny_step(s);
+        const int64_t ksteps = (K + step - 1) / step;
         const int64_t sk = effective_splits(ksteps, s.sk);
         if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
         s.sk = (int)sk;
         if (sk == 1) s.fr = 0;
         const int64_t strips = (N + kSkinnyCols - 1) / kSkinnyCols;
         if (s.fr && strips * (int64_t)sizeof(int) > (int64_t)kCounterBytes) return HGEMM_ERR_UNSUPPORTED;
-        p->skinny = skinny_kernel(mb, s.fr != 0);
+        p->skinny = skinny_kernel(mb, s.fr != 0, s.wv);
         if (!p->skinny) return HGEMM_ERR_UNSUPPORTED;
         GemmArgs& a = p->args;
         a.M = (int)M; a.N = (int)N; a.K = (int)K;
         a.lda = (int)p->lay.lda; a.ldb = (int)p->lay.ldb; a.ldc = (int)p->lay.ldc;
         a.tiles_m = 1; a.tiles_n = (int)strips;
         a.splits = (int)sk;
-        a.k_per_split = (int)(((ksteps + sk - 1) / sk) * kSkinnyStep);
+        a.k_per_split = (int)(((ksteps + sk - 1) / sk) * step);
         // workspace: [counters] [padded copies of A, B, C (plans on zero-padded operands)] [planes]
         auto up256s = [](size_t b) { return ((b + 255) / 256) * 256; };
         size_t pad_bytes = 0;
@@ -843,7 +852,7 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
     a.B = (const _Float16*)B;
     a.C = (_Float16*)C;
     if (plan->skinny) {
-        hipLaunchKernelGGL(plan->skinny, dim3((unsigned)a.tiles_n, (unsigned)a.splits), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(plan->skinny, dim3((unsigned)a.tiles_n, (unsigned)a.splits), dim3(64u * (unsigned)plan->spec.wv), 0, stream, a);
         if (a.splits > 1 && !plan->spec.fr) {
             if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
             const int64_t quads = M * (N / 4);
@@ -961,8 +970,8 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
     int64_t wg, lds, th;
     if (plan->skinny) {
         wg = (int64_t)plan->args.tiles_n * plan->args.splits;
-        lds = kSkinnyStep * kSkinnyCols * 2;
-        th = 256;
+        lds = 4 * 16 * (kSkinnyCols + 4) * 4;
+        th = 64 * plan->spec.wv;
     } else if (plan->entry) {
         wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
                            : (int64_t)plan->args.tiles_m * plan->args.tiles_n * plan->args.splits;
@@ -987,11 +996,12 @@ const char* hgemm_spec_help(void)
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
-            "skinny,sk=SPLITS[,fr=1]\n"
-            "    memory-bound kernel for M <= 64 rows of A (row-major B): workgroups of 4 waves take 128 columns and a\n"
-            "    K slab each and stream it in steps of 64 rows (loads one step ahead, transposed through LDS, 16x16x32\n"
-            "    matrix-core instructions with M on a 16-wide side); slabs are summed in slab order by the split-K\n"
-            "    reduction launch or, with fr = 1, inside the kernel by the workgroup that arrives last\n"
+            "skinny,sk=SPLITS[,fr=1][,wv=WAVES]\n"
+            "    memory-bound kernel for M <= 64 rows of A (row-major B): workgroups of wv = 4 (default), 8 or 16 waves\n"
+            "    take 128 columns and a K slab each and stream it in steps of 16 * wv rows; a wave takes 16 rows of a\n"
+            "    step, transposes its 4 x 8 blocks in registers for 16x16x16 matrix-core instructions (M on a 16-wide\n"
+            "    side; no LDS and no barrier in the main loop), the waves' sums meet once at the end; slabs are summed in\n"
+            "    slab order by the split-K reduction launch or, with fr = 1, by the workgroup that arrives last\n"
             "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16][,mi=16]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
@@ -1057,10 +1067,14 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
         if (l.b == HGEMM_ROW_MAJOR && M <= kSkinnyMaxM) {       // few rows: the streaming family competes
             for (int eff : skinny_split_candidates(N, K)) {
                 for (int fr = 0; fr <= ((eff > 1 && fused_delta_us(M, N, eff) < 1.0) ? 1 : 0); ++fr) {
-                    Spec s;
-                    s.fam = FAM_SKINNY; s.sk = (int)eff; s.fr = fr;
-                    out += spec_to_string(s);
-                    out += "\n";
+                    for (int wv : {4, 8, 16}) {
+                        if (wv == 16 && M > 32) continue;
+                        Spec s;
+                        s.fam = FAM_SKINNY; s.sk = (int)eff; s.fr = fr; s.wv = wv;
+                        if (effective_splits((K + skinny_step(s) - 1) / skinny_step(s), eff) != eff) continue;
+                        out += spec_to_string(s);
+                        out += "\n";
+                    }
                 }
             }
         }
@@ -1128,7 +1142,7 @@ hgemm_status_t hgemm_predict_us(int64_t M, int64_t N, int64_t K, const char* spe
     if (!parse_spec(spec, &s)) return HGEMM_ERR_INVALID_ARG;
     if (s.fam == FAM_SKINNY) {
         if (M > kSkinnyMaxM) return HGEMM_ERR_UNSUPPORTED;
-        const int64_t eff = effective_splits((K + kSkinnyStep - 1) / kSkinnyStep, s.sk);
+        const int64_t eff = effective_splits((K + skinny_step(s) - 1) / skinny_step(s), s.sk);
         *us = predict_skinny_us(M, N, K, eff, s.fr != 0 && eff > 1);
         return HGEMM_OK;
     }

@@ -3,13 +3,35 @@
 
 namespace hgemm {
 
-// Kernel for M <= 16 * mb (mb in {1, 2, 4}), with or without the fused reduction; null for other mb.
-void (*skinny_kernel(int mb, bool fused))(GemmArgs)
+namespace {
+#ifndef HGEMM_SKINNY_DEPTH
+#define HGEMM_SKINNY_DEPTH 2
+#endif
+constexpr int kDepth = HGEMM_SKINNY_DEPTH;      // steps of loads a wave keeps in flight (4 KiB each)
+
+template <int WAVES>
+void (*kernel_for(int mb, bool fused))(GemmArgs)
 {
     switch (mb) {
-        case 1: return fused ? skinny_gemm_kernel<1, true> : skinny_gemm_kernel<1, false>;
-        case 2: return fused ? skinny_gemm_kernel<2, true> : skinny_gemm_kernel<2, false>;
-        case 4: return fused ? skinny_gemm_kernel<4, true> : skinny_gemm_kernel<4, false>;
+        case 1: return fused ? skinny_gemm_kernel<1, true, kDepth, WAVES> : skinny_gemm_kernel<1, false, kDepth, WAVES>;
+        case 2: return fused ? skinny_gemm_kernel<2, true, kDepth, WAVES> : skinny_gemm_kernel<2, false, kDepth, WAVES>;
+        case 4:
+            // 16 waves leave a lane 128 registers: two blocks of A at most
+            if constexpr (WAVES < 16) return fused ? skinny_gemm_kernel<4, true, kDepth, WAVES> : skinny_gemm_kernel<4, false, kDepth, WAVES>;
+            break;
+    }
+    return nullptr;
+}
+}  // namespace
+
+// Kernel for M <= 16 * mb (mb in {1, 2, 4}) and workgroups of 4, 8 or 16 waves, with or without the fused
+// reduction; null for other values.
+void (*skinny_kernel(int mb, bool fused, int waves))(GemmArgs)
+{
+    switch (waves) {
+        case 4: return kernel_for<4>(mb, fused);
+        case 8: return kernel_for<8>(mb, fused);
+        case 16: return kernel_for<16>(mb, fused);
     }
     return nullptr;
 }

@@ -7,29 +7,41 @@
 // bytes, no long per-workgroup pipeline to fill and drain.  (A 32 MiB matrix is read cold in 6.3-6.7 us
 // that way, against 8-12 us for 128-256 workgroups with deep private pipelines.)  So:
 //
-//   * grid = column strips of 128 (x) by K slabs (y); a workgroup of 4 waves walks its slab in steps
-//     of 64 k-rows; one step is 64 x 128 halves = 16 KiB of B, four 16-byte loads per lane straight
-//     into registers, issued two steps ahead of use;
-//   * the step's block goes through LDS once (swizzled) so that the transposing read can hand the
-//     matrix cores 8 consecutive k per lane; v_mfma_f32_16x16x32_f16 with M on a 16-wide side and the
-//     operand roles swapped (the instruction computes a tile of C^T), so a lane owns 4 consecutive
-//     columns of one row of C; A (a few rows, cache resident) is loaded straight into registers;
-//   * K slabs are summed in slab order: either by the split-K reduction launch, or inside the kernel
-//     by the workgroup that arrives last at a strip (FUSED), exactly as in the large-tile kernel.
+//   * grid = column strips of 128 (x) by K slabs (y); a workgroup of WAVES waves walks its slab in
+//     steps of 16 * WAVES k-rows; a wave owns 16 rows of a step (wave w: rows 16 w .. 16 w + 15;
+//     16-lane group g of it: rows 4 g .. 4 g + 3) and all 128 columns: four 16-byte loads per lane
+//     straight into registers, DEPTH steps of them in flight;
+//   * no trip through LDS and no barrier in the main loop.  v_mfma_f32_16x16x16_f16 takes 4
+//     consecutive k per lane, which is what a lane has after its four loads (the same 8 columns of 4
+//     consecutive rows of B) once the 4 x 8 block of halves it holds is transposed inside its own
+//     registers (16 two-input byte selections); M sits on the instruction's other 16-wide side, A (a few
+//     rows, cache resident) is loaded straight into registers, 8 bytes per lane and step.  Every
+//     product the matrix cores form is a product A[m][k] * B[k][n] of the definition (rows of A
+//     beyond M and k-rows beyond the slab are read as zeros and only ever meet each other or rows
+//     that are not stored), so non-finite values stay in the elements the definition gives them;
+//   * the waves' sums meet once, at the end, through LDS (four waves at a time) and are added in wave
+//     order; K slabs are summed in slab order: either by the split-K reduction launch, or inside the
+//     kernel by the workgroup that arrives last at a strip (FUSED), exactly as in the large-tile kernel.
+//
+// (An earlier form staged each 64 x 128 block of B through LDS for a transposing read and
+// 16x16x32 instructions, with two barriers per step; this form is 3-30 % faster on every shape tried.)
 #pragma once
 #include "hgemm_mfma.hpp"
 
 namespace hgemm {
 
 constexpr int kSkinnyCols = 128;       // columns per workgroup
-constexpr int kSkinnyStep = 64;        // k-rows per step
 
 // MB = 16-row blocks of A a workgroup multiplies with every block of B it loads (M <= 16 * MB).
-template <int MB, bool FUSED>
-__global__ __launch_bounds__(256) void skinny_gemm_kernel(GemmArgs g)
+template <int MB, bool FUSED, int DEPTH, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(GemmArgs g)
 {
     typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-    __shared__ __attribute__((aligned(1024))) char lds[kSkinnyStep * kSkinnyCols * 2];
+    typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+    constexpr int STEP = 16 * WAVES;                           // k-rows per step of the workgroup
+    constexpr int PITCH = kSkinnyCols + 4;                     // floats per staged row of sums
+    static_assert(WAVES % 4 == 0, "the sums meet four waves at a time");
+    __shared__ __attribute__((aligned(16))) float red[4 * 16 * PITCH];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -38,135 +50,140 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(GemmArgs g)
     const int split = blockIdx.y;
     const int k_lo = split * g.k_per_split;
     const int k_hi = min(g.K, k_lo + g.k_per_split);
-    const int steps = (k_hi - k_lo + kSkinnyStep - 1) / kSkinnyStep;
+    const int steps = (k_hi - k_lo + STEP - 1) / STEP;
 
-    // Loads go through buffer descriptors: a lane whose row or column is out of range gets an
-    // out-of-range offset and reads zeros, so no load sits behind a branch and all of a step's loads
-    // are in flight together.
     const unsigned OOB = 0x80000000u;
     const __amdgpu_buffer_rsrc_t rsrcA =
         __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, (int)min((long long)g.M * g.lda * 2, 0x7fffffffLL), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB =
         __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, (int)min((long long)g.K * g.ldb * 2, 0x7fffffffLL), 0x00020000);
 
-    // ---- B: thread t loads 16 bytes (8 columns) of rows r, r+16, r+32, r+48 of a step
-    const int lc = t & 15, lr = t >> 4;
-    const bool col_ok = n0 + 8 * lc < g.N;
-    const unsigned b_off = (unsigned)(((k_lo + lr) * g.ldb + n0 + 8 * lc) * 2);
-    // LDS: rows of 256 bytes; the 16-byte chunk index is XORed with 4 * (row % 4) so that the four rows
-    // a transposing read touches lie in four different quarters of the bank window
-    char* wdst = lds + lr * 256 + ((lc ^ ((lr & 3) << 2)) * 16);
-
-    // ---- fragments.  B: within 16 lanes, lane s supplies row s / 4, columns 4 * (s % 4) .. + 3 of the
-    // wave's two 16-column blocks.  A: lane holds A[m = lane % 16][8 * (lane / 16) .. + 7].
-    const int s16 = lane & 15, grp = lane >> 4;
-    int rd_off[2];
-#pragma unroll
-    for (int cbi = 0; cbi < 2; ++cbi) {
-        const int chunk = 2 * (2 * wave + cbi) + ((s16 & 3) >> 1);
-        rd_off[cbi] = (8 * grp + (s16 >> 2)) * 256 + ((chunk ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
-    }
+    // lane (grp, c16): rows krow0 + STEP * step + s (s = 0..3) of B, columns n0 + 8 c16 .. + 7;
+    // A[16 mb + c16][krow0 + STEP * step .. + 3]
+    const int c16 = lane & 15, grp = lane >> 4;
+    const int krow0 = k_lo + 16 * wave + 4 * grp;
+    const bool col_ok = n0 + 8 * c16 < g.N;
+    const unsigned b_off = (unsigned)((krow0 * g.ldb + n0 + 8 * c16) * 2);
     unsigned a_off[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int m = 16 * mb + s16;
-        a_off[mb] = m < g.M ? (unsigned)((m * g.lda + k_lo + 8 * grp) * 2) : OOB;
+        const int m = 16 * mb + c16;
+        a_off[mb] = m < g.M ? (unsigned)((m * g.lda + krow0) * 2) : OOB;
     }
-
     auto load_b = [&](int step, uint4v (&q)[4]) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = k_lo + step * kSkinnyStep + lr + 16 * j;
-            const bool ok = col_ok && k < k_hi;
-            q[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, ok ? b_off + (unsigned)((step * kSkinnyStep + 16 * j) * g.ldb * 2) : OOB, 0, 0);
+        for (int s = 0; s < 4; ++s) {
+            const bool ok = col_ok && krow0 + step * STEP + s < k_hi;
+            q[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, ok ? b_off + (unsigned)((step * STEP + s) * g.ldb * 2) : OOB, 0, 0);
         }
     };
-    auto load_a = [&](int step, uint4v (&f)[MB][2]) {
+    // K is a multiple of 8 and krow0 of 4: the four k of a lane are in range together or not at all
+    auto load_a = [&](int step, uint2v (&f)[MB]) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int kc = 0; kc < 2; ++kc) {
-                const int k = k_lo + step * kSkinnyStep + 32 * kc + 8 * grp;
-                const bool ok = a_off[mb] != OOB && k < k_hi;
-                f[mb][kc] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, ok ? a_off[mb] + (unsigned)((step * kSkinnyStep + 32 * kc) * 2) : OOB, 0, 0);
-            }
+        for (int mb = 0; mb < MB; ++mb) {
+            const bool ok = a_off[mb] != OOB && krow0 + step * STEP < k_hi;
+            f[mb] = __builtin_amdgcn_raw_buffer_load_b64(rsrcA, ok ? a_off[mb] + (unsigned)(step * STEP * 2) : OOB, 0, 0);
+        }
     };
 
-    float4v acc[MB][2];
+    float4v acc[MB][8];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int cbi = 0; cbi < 2; ++cbi) acc[mb][cbi] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 8; ++j) acc[mb][j] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // two steps of loads in flight: set u holds step s with s % 2 == u (loads past the slab read zeros)
-    uint4v bq[2][4];
-    uint4v fa[2][MB][2];
-    load_b(0, bq[0]);
-    load_a(0, fa[0]);
-    load_b(1, bq[1]);
-    load_a(1, fa[1]);
-    for (int base = 0; base < steps; base += 2) {
+    // set u holds step s with s % DEPTH == u (loads past the slab read zeros)
+    uint4v bq[DEPTH][4];
+    uint2v fa[DEPTH][MB];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < DEPTH; ++u) {
+        load_b(u, bq[u]);
+        load_a(u, fa[u]);
+    }
+    for (int base = 0; base < steps; base += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
             const int step = base + u;
             if (step >= steps) break;
-            if (step > 0) __syncthreads();                   // every wave is done reading the previous block
+            // tb[j] = (B[k][n], B[k+1][n], B[k+2][n], B[k+3][n]) for the lane's column n = 8 c16 + j
+            uint2v tb[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) *(uint4v*)(wdst + j * 16 * 256) = bq[u][j];
-            half8 fa_cur[MB][2];
+            for (int d = 0; d < 4; ++d) {
+                const unsigned x0 = bq[u][0][d], x1 = bq[u][1][d], x2 = bq[u][2][d], x3 = bq[u][3][d];
+                tb[2 * d] = uint2v{(x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16)};
+                tb[2 * d + 1] = uint2v{(x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u)};
+            }
+            uint2v af[MB];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < MB; ++mb) af[mb] = fa[u][mb];
+            load_b(step + DEPTH, bq[u]);                     // refill this set
+            load_a(step + DEPTH, fa[u]);
 #pragma unroll
-                for (int kc = 0; kc < 2; ++kc) {
-                    union { uint4v i; half8 h; } cv;
-                    cv.i = fa[u][mb][kc];
-                    fa_cur[mb][kc] = cv.h;
-                }
-            __syncthreads();
-            load_b(step + 2, bq[u]);                         // refill this set: two steps ahead
-            load_a(step + 2, fa[u]);
+            for (int j = 0; j < 8; ++j) {
+                union { uint2v i; half4 h; } bv;
+                bv.i = tb[j];
 #pragma unroll
-            for (int kc = 0; kc < 2; ++kc) {
-#pragma unroll
-                for (int cbi = 0; cbi < 2; ++cbi) {
-                    const char* src = lds + kc * 32 * 256 + rd_off[cbi];
-                    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)HGEMM_LDS(src));
-                    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)HGEMM_LDS(src + 4 * 256));
-                    union { struct { short4v lo, hi; } s; half8 h; } cv;
-                    cv.s.lo = lo;
-                    cv.s.hi = hi;
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        acc[mb][cbi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cv.h, fa_cur[mb][kc], acc[mb][cbi], 0, 0, 0);
+                for (int mb = 0; mb < MB; ++mb) {
+                    union { uint2v i; half4 h; } av;
+                    av.i = af[mb];
+                    acc[mb][j] = __builtin_amdgcn_mfma_f32_16x16x16f16(bv.h, av.h, acc[mb][j], 0, 0, 0);
                 }
             }
         }
     }
 
-    // ---- epilogue.  acc[mb][cbi][v] = C[16 mb + lane % 16][n0 + 32 wave + 16 cbi + 4 (lane / 16) + v]
+    // ---- the waves' sums meet in LDS, one 16-row block of C and four waves at a time.
+    // acc[mb][j][r] belongs to C[16 mb + c16][n0 + 32 grp + 8 r + j]
     const bool direct = g.splits == 1;
+    float* mine = red + ((wave & 3) * 16 + c16) * PITCH + 32 * grp;
+    const bool summing = t < 256;                              // summing role: one row, 8 columns
+    const int orow = (t >> 4) & 15, ocol = 8 * (t & 15);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int m = 16 * mb + s16;
+        float4v s0 = float4v{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
-        for (int cbi = 0; cbi < 2; ++cbi) {
-            const int n = n0 + 32 * wave + 16 * cbi + 4 * grp;
-            if (m >= g.M || n >= g.N) continue;
-            if (direct) {
-                half4 o;
+        for (int w0 = 0; w0 < WAVES; w0 += 4) {
+            if (mb > 0 || w0 > 0) __syncthreads();             // the previous round's sums have been read
+            if (wave >= w0 && wave < w0 + 4) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[mb][cbi][e];
-                *(half4*)(g.C + (size_t)m * g.ldc + n) = o;
-            } else {
-                float* dst = g.partial + ((size_t)split * g.M + m) * g.N + n;
-                if (FUSED) {
-                    union { float4v f; unsigned long long u[2]; } w;
-                    w.f = acc[mb][cbi];
-                    store_agent((unsigned long long*)dst, w.u[0]);
-                    store_agent((unsigned long long*)dst + 1, w.u[1]);
-                } else {
-                    *(float4v*)dst = acc[mb][cbi];
+                for (int r = 0; r < 4; ++r) {
+                    *(float4v*)(mine + 8 * r) = float4v{acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]};
+                    *(float4v*)(mine + 8 * r + 4) = float4v{acc[mb][4][r], acc[mb][5][r], acc[mb][6][r], acc[mb][7][r]};
                 }
+            }
+            __syncthreads();
+            if (summing) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float* src = red + (w * 16 + orow) * PITCH + ocol;
+                    s0 += *(const float4v*)src;
+                    s1 += *(const float4v*)(src + 4);
+                }
+            }
+        }
+        const int m = 16 * mb + orow, n = n0 + ocol;
+        if (!summing || m >= g.M || n >= g.N) continue;
+        if (direct) {
+            half8 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = (_Float16)s0[e];
+                o[4 + e] = (_Float16)s1[e];
+            }
+            *(half8*)(g.C + (size_t)m * g.ldc + n) = o;
+        } else {
+            float* dst = g.partial + ((size_t)split * g.M + m) * g.N + n;
+            if (FUSED) {
+                union { float4v f; unsigned long long u[2]; } v0, v1;
+                v0.f = s0;
+                v1.f = s1;
+                store_agent((unsigned long long*)dst, v0.u[0]);
+                store_agent((unsigned long long*)dst + 1, v0.u[1]);
+                store_agent((unsigned long long*)dst + 2, v1.u[0]);
+                store_agent((unsigned long long*)dst + 3, v1.u[1]);
+            } else {
+                *(float4v*)dst = s0;
+                *(float4v*)(dst + 4) = s1;
             }
         }
     }
@@ -175,8 +192,8 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(GemmArgs g)
     // Fused reduction over the K slabs of this strip: device-coherent plane stores above, then the
     // workgroup that arrives last re-reads all planes in slab order (the result does not depend on who
     // is last), rounds once and stores.  Nobody waits for anybody.
-    __syncthreads();                                          // its release half waits for this wave's stores
-    int* flag = (int*)lds;
+    __syncthreads();
+    int* flag = (int*)red;
     if (t == 0) {
         int* ctr = g.counters + blockIdx.x;
         const int arrived = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -185,7 +202,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(GemmArgs g)
     }
     __syncthreads();
     if (*flag != g.splits - 1) return;
-    sum_split_planes<256, kSkinnyCols / 4>(g, 0, n0, g.M, t);
+    sum_split_planes<64 * WAVES, kSkinnyCols / 4>(g, 0, n0, g.M, t);
 }
 
 }  // namespace hgemm

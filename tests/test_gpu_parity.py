@@ -364,9 +364,11 @@ def skinny_specs(M, N, K):
 @pytest.mark.parametrize("shape", [(1, 264, 200), (16, 520, 1000), (7, 72, 4104), (33, 136, 328), (16, 4096, 32), (5, 8, 8), (64, 200, 776),
                                    (48, 1032, 2056), (17, 128, 64)])
 def test_skinny_family_every_spec_bit_exact(shape):
-    """The memory-bound family (128-column strips x K slabs in steps of 64 rows, 16x16x32 matrix-core instructions,
-    slabs summed in order by the reduction launch or by the last-arriving workgroup): ragged N, K not a multiple
-    of the step or of the slab count, one, two and four 16-row blocks of A, K shorter than a step."""
+    """The memory-bound family (128-column strips x K slabs in steps of 16 rows per wave, workgroups of 4, 8 or 16
+    waves, blocks of B transposed in registers for 16x16x16 matrix-core instructions, the waves' sums added in
+    wave order; slabs summed in order by the reduction launch or by the last-arriving workgroup): ragged N, K
+    not a multiple of the step or of the slab count, one, two and four 16-row blocks of A, K shorter than a
+    step."""
     name, a, b = wl.exact_family_for(shape, seed=12)
     ref = orc.hgemm(a, b)
     rng = np.random.default_rng([shape[0], shape[1], shape[2], 3])
@@ -374,7 +376,9 @@ def test_skinny_family_every_spec_bit_exact(shape):
     br = wl.uniform_pm1(rng, shape[2], shape[1])
     refr = orc.hgemm(ar, br)
     specs = skinny_specs(*shape)
-    for spec in specs + ["skinny,sk=3", "skinny,sk=5,fr=1"]:
+    assert any("wv=8" in x for x in specs) and any("wv=" not in x for x in specs)
+    # 16 waves leave a lane the registers for two 16-row blocks of A
+    for spec in specs + ["skinny,sk=3", "skinny,sk=5,fr=1", "skinny,sk=3,wv=8", "skinny,sk=2,fr=1,wv=16" if shape[0] <= 32 else "skinny,sk=2,fr=1,wv=8"]:
         c, before, after, desc = run_hgemm(a, b, spec=spec, guard=3)
         assert desc.startswith("skinny")
         assert_bit_exact(c, ref, f"{shape} {name} {desc}")
@@ -386,6 +390,9 @@ def test_skinny_family_every_spec_bit_exact(shape):
     # the fused reduction gives the bits of the two-launch reduction
     two, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=4")
     one, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=4,fr=1")
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    two, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=2,wv=8")
+    one, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=2,fr=1,wv=8")
     assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
 
 
@@ -399,7 +406,7 @@ def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals(
     C = torch.full((M, ldc), float("nan"), dtype=torch.float16, device="cuda")
     A[:, :K] = to_dev(a)
     B[:, :N] = to_dev(b)
-    for spec in ("skinny,sk=1", "skinny,sk=4", "skinny,sk=8,fr=1"):
+    for spec in ("skinny,sk=1", "skinny,sk=4", "skinny,sk=8,fr=1", "skinny,sk=1,wv=16", "skinny,sk=4,wv=8", "skinny,sk=8,fr=1,wv=8"):
         with hg.Plan(M, N, K, hg.Layouts.make(lda=lda, ldb=ldb, ldc=ldc), spec) as p:
             for rep in range(4):            # the arrival counters of the fused form come back to zero by themselves
                 C.fill_(float("nan"))
@@ -415,6 +422,42 @@ def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals(
         hg.Plan(8, 60, 64, None, "skinny,sk=1")
     with pytest.raises(hg.HgemmError):
         hg.Plan(65, 64, 64, None, "skinny,sk=1")
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(64, 64, 64, None, "skinny,sk=1,wv=16")          # 16 waves: two 16-row blocks of A at most
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(16, 64, 64, None, "skinny,sk=1,wv=5")
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(64, 64, 64, None, "mfma,bm=64,bn=64,bk=64,wm=2,wn=2,st=4,pf=3,sk=1,gm=8,wv=8")
+
+
+@pytest.mark.parametrize("spec", ["skinny,sk=1", "skinny,sk=2", "skinny,sk=3,fr=1", "skinny,sk=1,wv=8", "skinny,sk=1,wv=16"])
+def test_skinny_family_non_finite_and_subnormal_values(spec):
+    """NaN and infinities in A or B reach exactly the elements of C the definition gives them (a kernel that
+    multiplied a value of B with a zero that is not A's would spread them to neighbouring columns), an
+    infinity times a zero of the other operand is NaN, and subnormal inputs and results are kept."""
+    M, N, K = 13, 264, 200
+    a, b = wl.small_int_inputs((M, N, K), seed=9)
+    a = a.copy()
+    b = b.copy()
+    a[3, 5] = np.nan
+    a[10, 64] = np.inf
+    b[64, 7] = 0              # inf * 0 = NaN at C[10, 7]
+    b[17, 130] = np.inf       # a whole column of +-inf or, where A[m][17] == 0, NaN: column 130 only
+    b[199, 263] = np.nan
+    ref = orc.hgemm(a, b)
+    c, _, _, desc = run_hgemm(a, b, spec=spec)
+    assert np.array_equal(np.isnan(c), np.isnan(ref)), desc
+    fin = ~np.isnan(ref)
+    assert np.array_equal(c[fin].astype(np.float64), ref[fin].astype(np.float64)), desc
+    clean = [m for m in range(M) if m not in (3, 10)]          # rows of A without a non-finite value
+    assert np.isfinite(ref[clean, 129]).all() and np.isfinite(ref[clean, 131]).all() and not np.isfinite(ref[:, 130]).any()
+    rng = np.random.default_rng(78)
+    a2 = (rng.integers(-3, 4, size=(M, K)).astype(np.float64) * 2.0 ** -24).astype(np.float16)
+    b2 = wl.integers(rng, K, N, -2, 2)
+    ref2 = orc.hgemm(a2, b2)
+    assert (np.abs(ref2.astype(np.float64)) < 2.0 ** -14).all() and np.count_nonzero(ref2) > M * N // 2
+    c2, _, _, desc = run_hgemm(a2, b2, spec=spec)
+    assert_bit_exact(c2, ref2, "subnormal A: " + desc)
 
 
 def test_every_spec_real_inputs_within_tolerance():
