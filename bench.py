@@ -14,7 +14,7 @@ with all operands resident in HBM before the timed region.  After W untimed step
 timed between device synchronisations.  The K steps run shape-major: a shape's K calls go back to back
 on the stream (the paper's offline mode, Section 2.4.2) in five batches, each between its own pair of
 events on that stream (Section 2.4.1), so mean, median and minimum per-call times are real statistics
-of five measurements.  With --graph each batch is captured once in a HIP graph and replayed instead
+of five measurements (with K < 50: one batch, one event pair around the K calls, mean only).  With --graph each batch is captured once in a HIP graph and replayed instead
 (no host enqueue cost; pays only with long batches).  The last line printed is one JSON object:
 
   value         geometric mean over the 200 grid shapes of 2*M*N*K / (mean time per call), TFLOP/s
@@ -270,9 +270,10 @@ def metric_run(args):
     sh = stream.cuda_stream
     steps, warmup = max(1, args.steps), max(0, args.warmup)
     # An event record between batches costs the stream about 4 us (measured: 3.4 us per call of a 2.4 us
-    # kernel in batches of 4, 2.8 in batches of 10), so a batch holds at least 10 calls; with fewer than
-    # five batches per shape the median and minimum are not reported.
-    n_batches = min(5, max(1, steps // 10))
+    # kernel in batches of 4, 2.8 in batches of 10), so a batch holds at least 10 calls.  With at least 50
+    # steps a shape's calls go in five batches and the median and minimum over them are reported; with
+    # fewer they go in one batch (one event pair around all K calls) and those two fields are null.
+    n_batches = 5 if steps >= 50 else 1
     batch_sizes = [steps // n_batches + (1 if i < steps % n_batches else 0) for i in range(n_batches)]
 
     jobs = [("C4", s, False) for s in wl.c4_shapes()] + [("C2", s, False) for s in wl.C2_SHAPES] + \
@@ -537,7 +538,7 @@ def main():
     torch.cuda.synchronize()
 
     # five batches per shape, each between its own event pair: mean, median and minimum are real statistics
-    n_batches = 1 if args.graph else (min(5, args.steps) if args.per_call_events else min(5, max(1, args.steps // 10)))
+    n_batches = 1 if args.graph else (min(5, args.steps) if args.per_call_events else (5 if args.steps >= 50 else 1))
     batch_sizes = [args.steps // n_batches + (1 if i < args.steps % n_batches else 0) for i in range(n_batches)]
     pair = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in batch_sizes] for _ in sets]
     per_call = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]

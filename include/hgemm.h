@@ -68,6 +68,16 @@ typedef struct {
  * Allocates the plan's device workspace (split-K partial sums, stream-K
  * partial tiles, padded copies of unaligned operands) on the CURRENT device,
  * if the choice needs one.
+ * Size: the matrix-core kernels address an operand with 32-bit byte offsets,
+ * i.e. up to 2 GiB of it.  A problem with a larger A, B or C (dimensions and
+ * leading dimensions multiples of 8) is planned as a grid of blocks -- row
+ * blocks of A and C by column panels of B and C, each a plan of its own run
+ * on offset pointers, one after the other on the stream; a row-major B of
+ * that size is first copied, transposed, into the workspace (2*K*N bytes
+ * more), because only a K-contiguous B can be cut into panels of less than
+ * 2 GiB.  hgemm_plan_describe() then starts with "blocks,rows=R,cols=C".
+ * Only hgemm_plan() does this: an explicit spec returns UNSUPPORTED for
+ * such a problem, and hgemm_run_static() runs it on the generic kernel.
  * Errors: INVALID_ARG, UNSUPPORTED, ALLOC, ARCH.
  */
 hgemm_status_t hgemm_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K,

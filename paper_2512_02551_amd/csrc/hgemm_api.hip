@@ -166,6 +166,16 @@ struct hgemm_plan_s {
     size_t a_off, b_off, c_off; // byte offsets of the padded copies of A, B and C inside the workspace
     size_t bt_off;              // byte offset of the transposed copy of B (spec.tb)
     bool static_ws;             // the workspace is this device's static scratch array, not an allocation
+    // Operands beyond the reach of the kernels' 32-bit buffer offsets (2 GiB per operand): the problem runs
+    // as a grid of row blocks of A and C by column panels of B and C, each an ordinary plan of its own on
+    // offset pointers.  A row-major B of that size cannot be cut into panels that way (a panel still spans
+    // all K rows), so it is first copied, transposed, into the workspace (N x K, K contiguous), whose
+    // panels of rows are contiguous.
+    bool blocked = false;
+    bool blocked_bt = false;            // B is row-major and goes through the transposed copy
+    int64_t block_m = 0, block_n = 0;   // rows and columns per block
+    hgemm_layouts_t block_lay;          // layouts the blocks' plans were made for
+    hgemm_plan_s* sub[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};   // [last, shorter row block][last, narrower panel]
 };
 
 // ---------------------------------------------------------------------------
@@ -673,6 +683,8 @@ bool device_is_gfx950(int dev)
 
 // Fills *p (caller's storage) with a runnable plan.  static_ws: the workspace is the device's static
 // scratch array and nothing is allocated; otherwise the workspace is hipMalloc'ed and owned by the plan.
+hgemm_status_t init_blocked(hgemm_plan_s* p);
+
 hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, const char* spec_text,
                          bool static_ws)
 {
@@ -728,6 +740,8 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
                 fast = true;
             }
         }
+        const bool dims_aligned = !(N % 8 || K % 8 || l.lda % 8 || l.ldb % 8 || l.ldc % 8) && M < (1 << 24) && N < (1 << 24) && K < (1 << 24);
+        if (!fast && !static_ws && M > 0 && N > 0 && K > 0 && dims_aligned && init_blocked(p) == HGEMM_OK) return HGEMM_OK;
         if (!fast) {
             p->spec = Spec();
             st = finish_plan(p);
@@ -753,11 +767,97 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
     return st;
 }
 
+void destroy_blocks(hgemm_plan_s* p)
+{
+    for (auto& row : p->sub)
+        for (hgemm_plan_s*& q : row) {
+            if (!q) continue;
+            if (q->workspace && !q->static_ws && hipFree(q->workspace) != hipSuccess) (void)hipGetLastError();
+            delete q;
+            q = nullptr;
+        }
+    p->blocked = false;
+}
+
+// Plans a problem whose dimensions are aligned but whose operands reach 2 GiB as a grid of blocks (see
+// hgemm_plan_s).  On failure the plan is left as it was, for the generic kernel.
+hgemm_status_t init_blocked(hgemm_plan_s* p)
+{
+    const int64_t M = p->M, N = p->N, K = p->K;
+    const hgemm_layouts_t l = p->lay;
+    const int64_t lim = (int64_t)1 << 31;
+    auto down256 = [](int64_t v) { return v / 256 * 256; };
+    int64_t bm = std::min<int64_t>(M, std::min(down256((lim - 1) / (l.lda * 2) - 512), down256((((int64_t)1 << 33) - 1) / (l.ldc * 2))));
+    if (bm <= 0) return HGEMM_ERR_UNSUPPORTED;
+    hgemm_layouts_t sl = l;
+    // can the matrix-core kernels address B as it lies?  (asked of a block of 256 rows)
+    hgemm_layouts_t probe = l;
+    bool bt = false;
+    if (l.b == HGEMM_ROW_MAJOR && !fast_path_ok(std::min<int64_t>(bm, 256), N, K, probe)) {
+        if ((K + 63) / 64 > 65535) return HGEMM_ERR_UNSUPPORTED;          // grid of the transposing copy
+        bt = true;
+        sl.b = HGEMM_COL_MAJOR;
+        sl.ldb = K;
+    }
+    int64_t bn = N;
+    if (sl.b == HGEMM_COL_MAJOR) {
+        bn = std::min<int64_t>(N, down256((lim - 1) / (sl.ldb * 2) - 512));
+        if (bn <= 0) return HGEMM_ERR_UNSUPPORTED;
+    }
+    // blocks of equal size (a multiple of 256) rather than full ones and a sliver
+    auto even = [](int64_t total, int64_t most) {
+        const int64_t parts = (total + most - 1) / most;
+        return std::min(most, ((total + parts - 1) / parts + 255) / 256 * 256);
+    };
+    if (bm < M) bm = even(M, bm);
+    if (bn < N) bn = even(N, bn);
+    if (!fast_path_ok(bm, bn, K, sl)) return HGEMM_ERR_UNSUPPORTED;
+    p->blocked_bt = bt;
+    p->block_m = bm;
+    p->block_n = bn;
+    p->block_lay = sl;
+    const int64_t rows[2] = {M >= bm ? bm : 0, M % bm}, cols[2] = {N >= bn ? bn : 0, N % bn};
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            if (rows[i] == 0 || cols[j] == 0) continue;
+            hgemm_plan_s* q = new (std::nothrow) hgemm_plan_s();
+            hgemm_status_t st = q ? init_plan(q, rows[i], cols[j], K, &sl, nullptr, false) : HGEMM_ERR_ALLOC;
+            if (st == HGEMM_OK && q->blocked) st = HGEMM_ERR_UNSUPPORTED;
+            if (st != HGEMM_OK) {
+                if (q) {
+                    destroy_blocks(q);
+                    if (q->workspace && hipFree(q->workspace) != hipSuccess) (void)hipGetLastError();
+                    delete q;
+                }
+                destroy_blocks(p);
+                return st;
+            }
+            p->sub[i][j] = q;
+        }
+    p->spec = Spec();
+    p->entry = nullptr;
+    p->skinny = nullptr;
+    p->workspace = nullptr;
+    p->workspace_bytes = 0;
+    if (bt) {
+        const size_t bytes = (size_t)N * (size_t)K * 2;
+        if (hipMalloc(&p->workspace, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            p->workspace = nullptr;
+            destroy_blocks(p);
+            return HGEMM_ERR_ALLOC;
+        }
+        p->workspace_bytes = bytes;
+    }
+    p->blocked = true;
+    return HGEMM_OK;
+}
+
 hgemm_status_t make_plan(hgemm_plan_t* out, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts,
                          const char* spec_text)
 {
     if (!out) return HGEMM_ERR_INVALID_ARG;
-    hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s;
+    hgemm_plan_s* p = new (std::nothrow) hgemm_plan_s();
     if (!p) return HGEMM_ERR_ALLOC;
     const hgemm_status_t st = init_plan(p, M, N, K, layouts, spec_text, false);
     if (st != HGEMM_OK) { delete p; return st; }
@@ -794,6 +894,26 @@ static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const vo
         return hipGetLastError() == hipSuccess ? HGEMM_OK : HGEMM_ERR_LAUNCH;
     }
     if (!A || !B) return HGEMM_ERR_INVALID_ARG;
+
+    if (plan->blocked) {
+        const _Float16* Bp = (const _Float16*)B;
+        if (plan->blocked_bt) {
+            hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, stream,
+                               (const _Float16*)B, (_Float16*)plan->workspace, (int)K, (int)N, (int)plan->lay.ldb);
+            if (hipGetLastError() != hipSuccess) return HGEMM_ERR_LAUNCH;
+            Bp = (const _Float16*)plan->workspace;
+        }
+        const bool panels = plan->block_lay.b == HGEMM_COL_MAJOR;          // else every block takes all of B
+        for (int64_t m0 = 0; m0 < M; m0 += plan->block_m)
+            for (int64_t n0 = 0; n0 < N; n0 += plan->block_n) {
+                const hgemm_plan_s* q = plan->sub[M - m0 < plan->block_m ? 1 : 0][N - n0 < plan->block_n ? 1 : 0];
+                if (!q) return HGEMM_ERR_INVALID_ARG;
+                const hgemm_status_t st = run_plan(q, (const _Float16*)A + m0 * plan->lay.lda, panels ? Bp + n0 * plan->block_lay.ldb : Bp,
+                                                   (_Float16*)C + m0 * plan->lay.ldc + n0, hip_stream);
+                if (st != HGEMM_OK) return st;
+            }
+        return HGEMM_OK;
+    }
 
     void* const user_C = C;
     if (plan->padded) {
@@ -932,6 +1052,7 @@ hgemm_status_t hgemm_run_static(int64_t M, int64_t N, int64_t K, const hgemm_lay
 hgemm_status_t hgemm_destroy(hgemm_plan_t plan)
 {
     if (!plan) return HGEMM_OK;
+    destroy_blocks(plan);
     if (plan->workspace && !plan->static_ws) {
         if (hipFree(plan->workspace) != hipSuccess) (void)hipGetLastError();
     }
@@ -956,17 +1077,39 @@ const char* hgemm_status_string(hgemm_status_t status)
 hgemm_status_t hgemm_plan_describe(hgemm_plan_t plan, char* buf, size_t n)
 {
     if (!plan || !buf || n == 0) return HGEMM_ERR_INVALID_ARG;
-    const std::string s = spec_to_string(plan->spec) + (plan->padded ? ",pad=1" : "");
+    std::string s;
+    if (plan->blocked) {
+        char head[96];
+        snprintf(head, sizeof head, "blocks,rows=%lld,cols=%lld%s: ", (long long)plan->block_m, (long long)plan->block_n, plan->blocked_bt ? ",bt=1" : "");
+        const hgemm_plan_s* q = plan->sub[0][0] ? plan->sub[0][0] : plan->sub[1][0] ? plan->sub[1][0] : plan->sub[0][1] ? plan->sub[0][1] : plan->sub[1][1];
+        s = std::string(head) + (q ? spec_to_string(q->spec) : std::string("?"));
+    } else {
+        s = spec_to_string(plan->spec) + (plan->padded ? ",pad=1" : "");
+    }
     if (s.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
     memcpy(buf, s.c_str(), s.size() + 1);
     return HGEMM_OK;
 }
 
-size_t hgemm_plan_workspace_bytes(hgemm_plan_t plan) { return plan ? plan->workspace_bytes : 0; }
+size_t hgemm_plan_workspace_bytes(hgemm_plan_t plan)
+{
+    if (!plan) return 0;
+    size_t bytes = plan->workspace_bytes;
+    for (const auto& row : plan->sub)
+        for (const hgemm_plan_s* q : row)
+            if (q) bytes += q->workspace_bytes;
+    return bytes;
+}
 
 hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, int64_t* lds_bytes, int64_t* threads)
 {
     if (!plan) return HGEMM_ERR_INVALID_ARG;
+    if (plan->blocked) {                     // the figures of the most frequent kind of block
+        for (const auto& row : plan->sub)
+            for (hgemm_plan_s* q : row)
+                if (q) return hgemm_plan_launch_info(q, workgroups, lds_bytes, threads);
+        return HGEMM_ERR_INVALID_ARG;
+    }
     int64_t wg, lds, th;
     if (plan->skinny) {
         wg = (int64_t)plan->args.tiles_n * plan->args.splits;
