@@ -493,6 +493,46 @@ bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out, bool b_row_major =
     return found;
 }
 
+// Large problems the table does not hold: the tuned choice of the nearest shape that it does hold.
+// The cost model was fitted before the 16x16x32 kernels existed and never picks them, and on problems
+// of many tiles a neighbour's winner carries over (25 off-table shapes of at least 10^11 flop: the
+// neighbour's kernel is faster than the model's on 21, 4.7 % in the geometric mean) -- except where the
+// neighbour's tile fills the last round of workgroups much worse than the model's pick does (3000 x
+// 6144 x 4096: 288 tiles of 256 x 256 against 512 of 192 x 192, 18 % slower), which is what the
+// comparison of the two fill ratios below rules out (with it: 20 of 136 shapes change, those 7.5 %
+// faster in the geometric mean, none slower by more than 0.3 %).  Distance = sum over M, N, K of
+// |log2 ratio|, at most 1.5.
+double last_round_fill(const Spec& s, int64_t M, int64_t N)
+{
+    if (s.fam != FAM_MFMA || s.bm <= 0 || s.bn <= 0) return 0.0;
+    const int64_t cus = cu_count();
+    const int64_t t = ((M + s.bm - 1) / s.bm) * ((N + s.bn - 1) / s.bn) * std::max(1, s.sk);
+    return (double)t / (double)(((t + cus - 1) / cus) * cus);
+}
+
+bool neighbour_choice(int64_t M, int64_t N, int64_t K, bool b_col_major, const Spec& model, Spec* out)
+{
+    if (2.0 * (double)M * (double)N * (double)K < 3e10 || std::min(M, N) < 512 || model.fam != FAM_MFMA) return false;
+    const DispatchRow* rows = b_col_major ? kDispatchTableTN : kDispatchTable;
+    const size_t count = b_col_major ? sizeof(kDispatchTableTN) / sizeof(kDispatchTableTN[0]) : sizeof(kDispatchTable) / sizeof(kDispatchTable[0]);
+    auto lg = [](int64_t v) { return std::log2((double)std::max<int64_t>(v, 1)); };
+    double best = 1.5;
+    const DispatchRow* pick = nullptr;
+    for (size_t i = 0; i < count; ++i) {
+        const DispatchRow& r = rows[i];
+        if (r.m <= 0 || r.spec[0] == '\0') continue;
+        const double d = std::fabs(lg(M) - lg(r.m)) + std::fabs(lg(N) - lg(r.n)) + std::fabs(lg(K) - lg(r.k));
+        if (d <= best) { best = d; pick = &r; }
+    }
+    Spec near;
+    if (!pick || !parse_spec(pick->spec, &near) || near.fam != FAM_MFMA || near.tb) return false;
+    const MfmaEntry* e = find_entry(near);
+    if (!e || !tile_fits_problem(*e, M, N)) return false;
+    if (last_round_fill(near, M, N) < last_round_fill(model, M, N) - 0.1) return false;
+    *out = near;
+    return true;
+}
+
 // Gives the plan its workspace of p->workspace_bytes (static scratch or an allocation), points the
 // partial-sum and counter arguments into it and clears the counters of an allocated one.
 hgemm_status_t acquire_workspace(hgemm_plan_s* p, size_t partial_bytes, size_t ctr_bytes)
@@ -747,9 +787,16 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
             st = finish_plan(p);
         } else {
             const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
+            bool planned = false;
             if (!table_lookup(M, N, K, l.b == HGEMM_COL_MAJOR, &p->spec) || !packed) {
                 if (!model_choice(M, N, K, &p->spec, l.b == HGEMM_ROW_MAJOR)) p->spec = heuristic(M, N, K);
+                const Spec model = p->spec;
+                if (neighbour_choice(M, N, K, l.b == HGEMM_COL_MAJOR, model, &p->spec)) {
+                    planned = finish_plan(p) == HGEMM_OK;
+                    if (!planned) p->spec = model;
+                }
             }
+            if (planned) return HGEMM_OK;
             if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already
             st = finish_plan(p);
             if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
