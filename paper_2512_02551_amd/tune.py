@@ -49,6 +49,8 @@ def all_shapes(workloads):
         out += list(wl.C2_SHAPES)
     if "C3" in workloads:
         out += list(wl.C3_SHAPES)
+    if "C3L" in workloads:     # LLM projections of a larger model (beyond the five configurations)
+        out += list(wl.C3_LARGE_SHAPES)
     if "C4" in workloads:
         out += wl.c4_shapes()
     if "C5" in workloads:
@@ -111,6 +113,9 @@ def main():
                          "rewrite the table; no GPU work")
     ap.add_argument("--max-shapes", type=int, default=0)
     ap.add_argument("--max-k", type=int, default=0, help="only shapes with K <= this (re-tuning a slice of a workload)")
+    ap.add_argument("--shapes", default="", help="further shapes MxNxK,MxNxK,... tuned after the workloads' (use --workloads '' for these "
+                                                 "alone); those with fewer than 312 flop per byte of operands are timed with rotating operand sets")
+    ap.add_argument("--max-m", type=int, default=0, help="only shapes with M <= this (e.g. the shapes the skinny family can run)")
     ap.add_argument("--max-flop", type=float, default=0.0, help="only shapes with 2*M*N*K <= this")
     ap.add_argument("--min-flop", type=float, default=0.0, help="only shapes with 2*M*N*K >= this")
     ap.add_argument("--graph-below-flop", type=float, default=2e10,
@@ -129,7 +134,7 @@ def main():
     ap.add_argument("--only-recorded-with", default="",
                     help="with --candidates-from: tune only the shapes that have a spec containing this text on record")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
-    ap.add_argument("--cold-workloads", default="C3",
+    ap.add_argument("--cold-workloads", default="C3,C3L",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
                          "so that the choice is made for data coming from HBM, not from the last-level cache")
     args = ap.parse_args()
@@ -165,10 +170,14 @@ def main():
     elif os.path.exists(args.out_log):
         os.remove(args.out_log)
 
-    shapes = [s for s in all_shapes(args.workloads.split(",")) if s not in done]
+    extra = [tuple(int(v) for v in item.split("x")) for item in args.shapes.split(",") if item]
+    shapes = [s for s in all_shapes(args.workloads.split(",")) + [e for e in extra if e not in all_shapes(args.workloads.split(","))] if s not in done]
     cold_shapes = set(all_shapes([w for w in args.cold_workloads.split(",") if w])) if args.cold_workloads else set()
+    cold_shapes |= {(m, n, k) for (m, n, k) in extra if m * n * k / (m * k + k * n + m * n) < 312}
     if args.max_k:
         shapes = [s for s in shapes if s[2] <= args.max_k]
+    if args.max_m:
+        shapes = [s for s in shapes if s[0] <= args.max_m]
     if args.max_flop:
         shapes = [s for s in shapes if 2.0 * s[0] * s[1] * s[2] <= args.max_flop]
     if args.min_flop:

@@ -35,6 +35,12 @@ C2_SHAPES: Tuple[Shape, ...] = tuple((n, n, n) for n in (1024, 2048, 4096, 8192)
 C3_M: Tuple[int, ...] = (1, 16, 64, 128, 512)
 C3_NK: Tuple[Tuple[int, int], ...] = ((4096, 4096), (11008, 4096), (4096, 11008), (14336, 4096))
 C3_SHAPES: Tuple[Shape, ...] = tuple((m, n, k) for (n, k) in C3_NK for m in C3_M)
+# Not one of the five configurations: the same kind of shape for a model four times the size (hidden
+# width 8192, feed-forward width 28672), inputs by the C3 recipe.  Weights of 128-448 MiB show what
+# the memory-bound kernels reach when launch and ramp-up no longer weigh on a 10-20 us call.
+C3_LARGE_M: Tuple[int, ...] = (1, 16, 64)
+C3_LARGE_NK: Tuple[Tuple[int, int], ...] = ((8192, 8192), (28672, 8192), (8192, 28672))
+C3_LARGE_SHAPES: Tuple[Shape, ...] = tuple((m, n, k) for (n, k) in C3_LARGE_NK for m in C3_LARGE_M)
 C5_SHAPES: Tuple[Shape, ...] = ((16384, 16384, 8192), (16384, 16384, 16384))
 C5_INT_SHAPE: Shape = (16384, 16384, 128)
 
