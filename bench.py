@@ -73,10 +73,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="ALL", choices=["ALL", "C1", "C2", "C3", "C3L", "C4", "C5", "P"],
+    ap.add_argument("--workload", default="ALL", choices=["ALL", "C1", "C2", "C3", "C3L", "C3O", "C4", "C5", "P"],
                     help="ALL: the metric (grid C4 as the value, C2, C5 warm and C3 cold beside it); C1..C5: one "
-                         "benchmark configuration; C3L: the C3 kind of shape for a model four times the size (use with "
-                         "--cold); P: the paper's full grid, all 1000 triples over "
+                         "benchmark configuration; C3L, C3O: the C3 kind of shape for a model four times the size and for other "
+                         "model widths (use with --cold); P: the paper's full grid, all 1000 triples over "
                          "{64..16384}^3 (Abstract), timed shape by shape beside torch.matmul")
     ap.add_argument("--cold", action="store_true", help="rotate operand sets so caches are cold")
     ap.add_argument("--shapes", default="", help="with --workload C2..C5: time these shapes (MxNxK,MxNxK,...) instead of the workload's own, "
@@ -119,6 +119,8 @@ def workload_shapes(name):
         return list(wl.C3_SHAPES), wl.c3_inputs
     if name == "C3L":
         return list(wl.C3_LARGE_SHAPES), wl.c3_inputs
+    if name == "C3O":
+        return list(wl.C3_OTHER_SHAPES), wl.c3_inputs
     if name == "C4":
         return wl.c4_shapes(), wl.c4_inputs
     return list(wl.C5_SHAPES), wl.c5_inputs
@@ -478,7 +480,7 @@ def main():
 
     shapes, make_inputs = workload_shapes(args.workload)
     if args.shapes:
-        if args.workload not in ("C2", "C3", "C3L", "C4", "C5"):
+        if args.workload not in ("C2", "C3", "C3L", "C3O", "C4", "C5"):
             sys.exit("bench.py: --shapes needs --workload C2, C3, C4 or C5 (whose input recipe it uses)")
         shapes = [tuple(int(v) for v in item.split("x")) for item in args.shapes.split(",") if item]
         if any(len(sh_) != 3 or min(sh_) < 1 for sh_ in shapes):
@@ -644,6 +646,8 @@ def main():
             "workload": {"C1": "single 256^3, uniform[-1,1]",
                          "C2": "square HGEMM sweep M=N=K in {1024,2048,4096,8192}, entries N(0,1)/sqrt(K)",
                          "C3": "LLM-projection skinny shapes, A~N(0,1), B~N(0,0.02^2)",
+                         "C3O": "LLM-projection skinny shapes of other model widths (M in {1,16,64,128,512}; 5120/13824/15360, 6144x4096, "
+                                "10240x8192; beyond the five configurations), A~N(0,1), B~N(0,0.02^2)",
                          "C3L": "LLM-projection skinny shapes of a larger model (M in {1,16,64}, widths 8192 and 28672; beyond the five "
                                 "configurations), A~N(0,1), B~N(0,0.02^2)",
                          "C4": "200-shape grid from {64..12288}^3, uniform[-1,1]",

@@ -799,9 +799,16 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
             if (planned) return HGEMM_OK;
             if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already
             st = finish_plan(p);
-            if (st == HGEMM_ERR_UNSUPPORTED) {       // a table row naming a kernel this build lacks
-                p->spec = heuristic(M, N, K);
+            if (st == HGEMM_ERR_UNSUPPORTED) {
+                // a table row naming a kernel this build lacks, or a row of the NN table, consulted for a
+                // column-major B, that names the streaming family (row-major B only): the cost model decides
+                if (!model_choice(M, N, K, &p->spec, l.b == HGEMM_ROW_MAJOR)) p->spec = heuristic(M, N, K);
+                if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;
                 st = finish_plan(p);
+                if (st == HGEMM_ERR_UNSUPPORTED) {
+                    p->spec = heuristic(M, N, K);
+                    st = finish_plan(p);
+                }
             }
             if (st != HGEMM_OK && st != HGEMM_ERR_WORKSPACE && p->padded) {   // e.g. no memory for the padded copies: the generic kernel needs none
                 p->padded = false;

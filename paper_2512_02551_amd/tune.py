@@ -51,6 +51,8 @@ def all_shapes(workloads):
         out += list(wl.C3_SHAPES)
     if "C3L" in workloads:     # LLM projections of a larger model (beyond the five configurations)
         out += list(wl.C3_LARGE_SHAPES)
+    if "C3O" in workloads:     # LLM projections of other model widths (beyond the five configurations)
+        out += list(wl.C3_OTHER_SHAPES)
     if "C4" in workloads:
         out += wl.c4_shapes()
     if "C5" in workloads:
@@ -134,7 +136,7 @@ def main():
     ap.add_argument("--only-recorded-with", default="",
                     help="with --candidates-from: tune only the shapes that have a spec containing this text on record")
     ap.add_argument("--merge-into", default="", help="after tuning, replace the rows of these shapes in this log and rewrite the table from it")
-    ap.add_argument("--cold-workloads", default="C3,C3L",
+    ap.add_argument("--cold-workloads", default="C3,C3L,C3O",
                     help="workloads whose shapes are timed with rotating operand sets (> 768 MiB between reuses), "
                          "so that the choice is made for data coming from HBM, not from the last-level cache")
     args = ap.parse_args()

@@ -203,22 +203,26 @@ def test_large_shapes_off_the_table_take_a_tuned_neighbours_kernel_or_the_models
     print(f"{shape} {'TN' if b_col_major else 'NN'}: {desc}")
 
 
-@pytest.mark.parametrize("nk", wl.C3_LARGE_NK, ids=lambda nk: f"N{nk[0]}xK{nk[1]}")
-def test_llm_projections_of_a_larger_model(nk):
-    """The C3 kind of shape for widths 8192 and 28672 (beyond the five configurations; C3's input recipe): these are
-    the rows of the dispatch table that the streaming kernel family holds for M = 1 and 16.  One B per (N, K), the
-    first M rows of one A; sampled positions against the oracle, and the exact-integer family bit for bit."""
+@pytest.mark.parametrize("nk", [*wl.C3_LARGE_NK, *wl.C3_OTHER_NK], ids=lambda nk: f"N{nk[0]}xK{nk[1]}")
+def test_llm_projections_of_other_models(nk):
+    """The C3 kind of shape for other model widths (beyond the five configurations; C3's input recipe): widths
+    8192 and 28672, whose rows for M = 1 and 16 the streaming kernel family holds in the dispatch table, and
+    5120 / 13824 / 15360, 6144 x 4096, 10240 x 8192.  One B per (N, K), the first M rows of one A; sampled
+    positions against the oracle, and the exact-integer family bit for bit."""
     N, K = nk
-    a64, b = wl.c3_inputs((64, N, K))
-    _, ai64, bi = wl.exact_family_for((64, N, K), seed=41)
-    for M in wl.C3_LARGE_M:
-        a = np.ascontiguousarray(a64[:M])
+    large = nk in wl.C3_LARGE_NK
+    ms = wl.C3_LARGE_M if large else wl.C3_M
+    top = max(ms)
+    a_top, b = wl.c3_inputs((top, N, K))
+    _, ai_top, bi = wl.exact_family_for((top, N, K), seed=41)
+    for M in ms:
+        a = np.ascontiguousarray(a_top[:M])
         c, before, after, desc = run_hgemm(a, b, guard=1)
-        if M <= 16:
+        if large and M <= 16:
             assert desc.startswith("skinny"), desc
         _check_sampled(a, b, c, 2000, f"{(M, N, K)} {desc}")
         assert np.isnan(before).all() and np.isnan(after).all(), desc
-        ai = np.ascontiguousarray(ai64[:M])
+        ai = np.ascontiguousarray(ai_top[:M])
         ci, _, _, _ = run_hgemm(ai, bi)
         ii, jj = wl.sample_positions((M, N, K), 2000, seed=8)
         ref = orc.hgemm_at(ai, bi, ii, jj)
@@ -226,3 +230,14 @@ def test_llm_projections_of_a_larger_model(nk):
         assert sel.mean() > 0.5
         assert np.array_equal(ci[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"{(M, N, K)} {desc}"
         print(f"{(M, N, K)}: {desc}")
+    # column-major B finds no row of its own for these shapes; the NN row names the streaming family, which needs a
+    # row-major B, so the cost model decides
+    if large:
+        M = 16
+        ai = np.ascontiguousarray(ai_top[:M])
+        ci, _, _, desc = run_hgemm(ai, np.ascontiguousarray(bi.T), b_col_major=True)
+        assert desc.startswith("mfma,"), desc
+        ii, jj = wl.sample_positions((M, N, K), 2000, seed=9)
+        ref = orc.hgemm_at(ai, bi, ii, jj)
+        sel = np.abs(ref.astype(np.float64)) <= 2048
+        assert np.array_equal(ci[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), f"TN {(M, N, K)} {desc}"

@@ -41,6 +41,12 @@ C3_SHAPES: Tuple[Shape, ...] = tuple((m, n, k) for (n, k) in C3_NK for m in C3_M
 C3_LARGE_M: Tuple[int, ...] = (1, 16, 64)
 C3_LARGE_NK: Tuple[Tuple[int, int], ...] = ((8192, 8192), (28672, 8192), (8192, 28672))
 C3_LARGE_SHAPES: Tuple[Shape, ...] = tuple((m, n, k) for (n, k) in C3_LARGE_NK for m in C3_LARGE_M)
+# Also outside the five configurations: projections of other common model widths (hidden 5120 with
+# feed-forward 13824 and a fused 3 x 5120 attention projection; grouped-query attention projections of
+# 6144 x 4096 and 10240 x 8192), C3's token counts and input recipe.  They are in the dispatch table so
+# that a user of such a model gets measured choices rather than modelled ones.
+C3_OTHER_NK: Tuple[Tuple[int, int], ...] = ((5120, 5120), (13824, 5120), (5120, 13824), (15360, 5120), (6144, 4096), (10240, 8192))
+C3_OTHER_SHAPES: Tuple[Shape, ...] = tuple((m, n, k) for (n, k) in C3_OTHER_NK for m in C3_M)
 C5_SHAPES: Tuple[Shape, ...] = ((16384, 16384, 8192), (16384, 16384, 16384))
 C5_INT_SHAPE: Shape = (16384, 16384, 128)
 
