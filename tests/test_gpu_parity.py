@@ -522,6 +522,42 @@ def test_small_m_and_tiny_shapes_default_plan(shape):
     assert np.isnan(before).all() and np.isnan(after).all()
 
 
+def _random_shapes(count, seed):
+    """Dimensions log-uniform over 1 .. 4096, two thirds of them rounded to multiples of 8 (the matrix-core path),
+    the rest left as drawn (padded copies or the generic kernel); M*N*K bounded so that the oracle stays quick."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        dims = [int(2.0 ** rng.uniform(0.0, 12.0)) for _ in range(3)]
+        if rng.random() < 2.0 / 3.0:
+            dims[1] = max(8, dims[1] // 8 * 8)
+            dims[2] = max(8, dims[2] // 8 * 8)
+        if dims[0] * dims[1] * dims[2] <= 3e8:
+            out.append(tuple(dims))
+    return out
+
+
+def test_random_shapes_whatever_the_planner_picks_both_layouts():
+    """160 seeded random shapes through hgemm_plan (dispatch table never hit: cost model, nearest tuned shape,
+    streaming family, padded copies, generic kernel), row-major and column-major B: bit-exact on {-2..2} inputs
+    wherever |C| <= 2048, nothing written outside C, and every family of plan seen at least once."""
+    seen = set()
+    for i, shape in enumerate(_random_shapes(160, 2024)):
+        M, N, K = shape
+        rng = np.random.default_rng([i, M, N, K])
+        a = wl.integers(rng, M, K, -2, 2)
+        b = wl.integers(rng, K, N, -2, 2)
+        ref = orc.hgemm(a, b)
+        sel = np.abs(ref.astype(np.float64)) <= 2048
+        tn = i % 3 == 2
+        c, before, after, desc = run_hgemm(a, np.ascontiguousarray(b.T) if tn else b, b_col_major=tn, guard=2)
+        assert np.array_equal(c[sel].astype(np.float64), ref[sel].astype(np.float64)), f"{shape} {'TN' if tn else 'NN'} {desc}"
+        assert not np.isnan(c).any(), f"{shape} {desc}: part of C not written"
+        assert np.isnan(before).all() and np.isnan(after).all(), f"{shape} {desc}: wrote outside C"
+        seen.add("pad" if "pad=1" in desc else desc.split(",")[0])
+    assert {"mfma", "skinny", "generic", "pad"} <= seen, seen
+
+
 @pytest.mark.parametrize("shape", [(3, 5, 7), (17, 9, 33), (65, 130, 100), (1, 1, 1), (129, 63, 100)])
 def test_small_unaligned_shapes_take_generic_kernel(shape):
     M, N, K = shape
