@@ -457,6 +457,8 @@ def main():
               "the library has no multi-GPU path (each GPU would run it on its own block of C)", file=sys.stderr)
         sys.exit(2)
 
+    if args.shapes and args.workload in ("ALL", "P", "C1"):
+        sys.exit("bench.py: --shapes needs --workload C2, C3, C3L, C3O, C4 or C5 (whose input recipe it uses)")
     if args.workload == "P":
         paper_grid(args)
         return
