@@ -401,14 +401,17 @@ double predict_us(int64_t Mi, int64_t Ni, int64_t Ki, int bm, int bn, int bk, in
 // time of B at a rate that grows with the number of workgroups in flight, the partial-plane traffic,
 // and the reduction (a second launch, or the tail of the fused form).
 struct SkinnyModel {
-    double t0 = 2.5;          // us: launch and first bytes
-    double bw = 5600.0;       // bytes/ns: chip-wide streaming rate with enough workgroups
-    double wg_bw = 25.0;      // bytes/ns one workgroup sustains (its two steps of loads in flight)
-    double round = 1.0;       // us of fill and drain per round of resident workgroups (3 per compute unit)
-    double part_bw = 2500.0;  // bytes/ns for writing and re-reading fp32 planes
-    double red2 = 3.2;        // us: second launch of the two-kernel reduction
-    double red1 = 2.4;        // us: tail of the fused reduction
-    double red1_per_mb = 0.9; // us more per MiB of planes when they are stored device-coherently
+    // fitted (soft-L1 on log time, rms 0.095) to 107 measured (shape, slabs, fused) points of the register-transposing
+    // kernel: M = 1, 16 on the C3 weights with every slab count, M = 1 .. 64 on weights of 112-448 MiB
+    double t0 = 4.2;          // us: launch, first bytes and the waves' meeting at the end
+    double bw = 6770.0;       // bytes/ns: chip-wide streaming rate with enough workgroups
+    double wg_bw = 37.7;      // bytes/ns one workgroup sustains (its two steps of loads in flight)
+    double round = 1.44;      // us of fill and drain per round of resident workgroups (3 per compute unit)
+    double part_bw = 8750.0;  // bytes/ns for writing and re-reading fp32 planes
+    double red2 = 1.93;       // us: second launch of the two-kernel reduction
+    double red1 = 1.57;       // us: tail of the fused reduction
+    double red1_per_mb = 5.0; // us more per MiB of planes when they are stored device-coherently
+    double per_block = 0.28;  // relative cost of every further 16-row block of A (registers: fewer resident waves)
 };
 const SkinnyModel kSkinny;
 
@@ -420,7 +423,7 @@ double predict_skinny_us(int64_t M, int64_t N, int64_t K, int64_t sk, bool fused
     const double rate = std::min(g.bw, g.wg_bw * wgs);
     const double planes = sk > 1 ? (double)sk * M * N * 4.0 : 0.0;
     const double mblocks = M <= 16 ? 1.0 : M <= 32 ? 2.0 : 4.0;
-    double t = g.t0 + 2.0 * (double)K * N / rate * 1e-3 * (1.0 + 0.08 * (mblocks - 1.0)) + std::ceil(wgs / (3.0 * (double)cu_count())) * g.round +
+    double t = g.t0 + 2.0 * (double)K * N / rate * 1e-3 * (1.0 + g.per_block * (mblocks - 1.0)) + std::ceil(wgs / (3.0 * (double)cu_count())) * g.round +
                2.0 * planes / g.part_bw * 1e-3;
     if (sk > 1) t += fused ? g.red1 + g.red1_per_mb * planes / 1048576.0 : g.red2;
     return t;
@@ -470,6 +473,14 @@ bool model_choice(int64_t M, int64_t N, int64_t K, Spec* out, bool b_row_major =
             }
         }
     }
+    // The large-tile model below was fitted to timings with the operands warm in the last-level cache wherever
+    // they fit it, the streaming family's to operands streamed from HBM; the two are not comparable for a few
+    // rows of A against weights that no cache holds (256 MiB and more).  Measured from HBM at M <= 32 the
+    // streaming family is the faster one there (8 and 32 x 28672 x 8192: 81 / 94 us against 128 for the large-tile
+    // pick; 8192 x 28672: 77 / 87 against 116; 4 x 16384 x 16384: 87 us, 77 % of the HBM rate); for weights of
+    // 128-160 MiB the two families are level at M = 1 and the 32-row tiles ahead from M = 16 on (32 x 10240 x 8192:
+    // 36 us against 51), so those stay with the model.
+    if (found && M <= 32 && 2.0 * (double)K * (double)N >= 256.0 * 1048576.0) return true;
     for (const MfmaEntry& e : registry()) {
         if (e.deep || e.mi != 32) continue;          // the cost model was not fitted to these kernels: the tuner's business
         if (!tile_fits_problem(e, M, N)) continue;
