@@ -538,11 +538,13 @@ def _random_shapes(count, seed):
 
 
 def test_random_shapes_whatever_the_planner_picks_both_layouts():
-    """160 seeded random shapes through hgemm_plan (dispatch table never hit: cost model, nearest tuned shape,
-    streaming family, padded copies, generic kernel), row-major and column-major B: bit-exact on {-2..2} inputs
+    """160 seeded random shapes and two large skinny ones through hgemm_plan (dispatch table never hit: cost model,
+    nearest tuned shape, streaming family, padded copies, generic kernel), row-major and column-major B: bit-exact on {-2..2} inputs
     wherever |C| <= 2048, nothing written outside C, and every family of plan seen at least once."""
     seen = set()
-    for i, shape in enumerate(_random_shapes(160, 2024)):
+    # two shapes with a few rows of A against weights of 256 MiB: what the planner gives to the streaming family
+    shapes = _random_shapes(160, 2024) + [(8, 16384, 8192), (24, 8192, 16384)]
+    for i, shape in enumerate(shapes):
         M, N, K = shape
         rng = np.random.default_rng([i, M, N, K])
         a = wl.integers(rng, M, K, -2, 2)
