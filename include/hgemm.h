@@ -206,6 +206,23 @@ const char* hgemm_spec_help(void);
 hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K,
                                 const hgemm_layouts_t* layouts, char* buf, size_t n);
 
+/* What hgemm_plan() would choose for a problem, and why, without a device
+ * (host only; nothing is allocated or launched): buf receives one of
+ *   "table: SPEC"      the row of the layout's dispatch table (Section 5: one
+ *                      configuration per (M,N,K), here from timed runs)
+ *   "neighbour: SPEC"  a large problem the table does not hold: the kernel
+ *                      tuned for the nearest shape it does hold
+ *   "model: SPEC"      the fitted cost model's pick;  "rules: SPEC" its last
+ *                      resort
+ *   "blocks,rows=R,cols=C[,bt=1]"   operands of 2 GiB and more
+ *   "generic"          unaligned and too small to pad;  "empty"  M, N or K = 0
+ * with ",pad=1" appended when the kernel would run on zero-padded copies.
+ * hgemm_plan() then still has to set the choice up on the device; where that
+ * fails (a kernel this build lacks, no memory) it falls back as documented
+ * there.  Errors: INVALID_ARG (also when buf is too small), UNSUPPORTED.    */
+hgemm_status_t hgemm_plan_choice(int64_t M, int64_t N, int64_t K,
+                                 const hgemm_layouts_t* layouts, char* buf, size_t n);
+
 /* The planner's cost model: predicted microseconds of one call of `spec` (an "mfma" spec without
  * tb/sm) on an M x N x K problem.  hgemm_plan() picks the compiled configuration and split factor
  * with the smallest prediction when its measured table has no row for the shape (Section 6 reads

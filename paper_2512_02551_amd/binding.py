@@ -17,7 +17,7 @@ EXPORTS = (
     "hgemm_plan", "hgemm_plan_override", "hgemm_run", "hgemm_destroy", "hgemm_status_string",
     "hgemm_plan_describe", "hgemm_plan_workspace_bytes", "hgemm_plan_launch_info", "hgemm_spec_help",
     "hgemm_candidates", "hgemm_tiles", "hgemm_padded", "hgemm_tile_of_workgroup",
-    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us", "hgemm_run_static", "hgemm_run_many",
+    "hgemm_calibrate_mfma", "hgemm_calibrate_hbm_read", "hgemm_predict_us", "hgemm_run_static", "hgemm_run_many", "hgemm_plan_choice",
 )
 
 STATIC_SCRATCH_BYTES = 64 << 20      # HGEMM_STATIC_SCRATCH_BYTES of include/hgemm.h
@@ -91,6 +91,8 @@ def load() -> ctypes.CDLL:
     lib.hgemm_spec_help.argtypes = []
     lib.hgemm_candidates.restype = ci
     lib.hgemm_candidates.argtypes = [i64, i64, i64, lp, ctypes.c_char_p, ctypes.c_size_t]
+    lib.hgemm_plan_choice.restype = ci
+    lib.hgemm_plan_choice.argtypes = [i64, i64, i64, lp, ctypes.c_char_p, ctypes.c_size_t]
     lib.hgemm_predict_us.restype = ci
     lib.hgemm_predict_us.argtypes = [i64, i64, i64, cp, ctypes.POINTER(ctypes.c_double)]
     lib.hgemm_tiles.restype = i64
@@ -144,6 +146,15 @@ def candidates(M: int, N: int, K: int, layouts: Optional[Layouts] = None) -> lis
     if st != 0:
         raise HgemmError(st, "hgemm_candidates")
     return [s for s in buf.value.decode().split("\n") if s]
+
+
+def plan_choice(M: int, N: int, K: int, layouts: Optional[Layouts] = None) -> str:
+    """What hgemm_plan would choose for the problem, and from where ("table: ...", "model: ..."); host only."""
+    buf = ctypes.create_string_buffer(512)
+    st = load().hgemm_plan_choice(M, N, K, ctypes.byref(layouts) if layouts is not None else None, buf, len(buf))
+    if st != 0:
+        raise HgemmError(st, "hgemm_plan_choice")
+    return buf.value.decode()
 
 
 def predict_us(M: int, N: int, K: int, spec: str) -> float:

@@ -289,7 +289,11 @@ bool table_lookup(int64_t M, int64_t N, int64_t K, bool b_col_major, Spec* out)
         }
     for (size_t i = 0; i < sizeof(kDispatchTable) / sizeof(kDispatchTable[0]); ++i) {
         const DispatchRow& r = kDispatchTable[i];
-        if (r.m == M && r.n == N && r.k == K) return r.spec[0] != '\0' && parse_spec(r.spec, out);
+        if (r.m == M && r.n == N && r.k == K) {
+            // a row of the NN table serves a column-major B only if it names the large-tile family (the streaming
+            // family reads row-major B)
+            return r.spec[0] != '\0' && parse_spec(r.spec, out) && !(b_col_major && out->fam != FAM_MFMA);
+        }
     }
     return false;
 }
@@ -734,6 +738,29 @@ bool device_is_gfx950(int dev)
 
 // Fills *p (caller's storage) with a runnable plan.  static_ws: the workspace is the device's static
 // scratch array and nothing is allocated; otherwise the workspace is hipMalloc'ed and owned by the plan.
+// The specialisation the planner tries first for an aligned problem of less than 2 GiB per operand, and where
+// it comes from: the layout's dispatch table (packed leading dimensions only), else the cost model, whose pick a
+// large problem trades for the kernel tuned for the nearest shape of the table (neighbour_choice); `fallback` is
+// the model's pick in that last case, should the neighbour's kernel refuse the shape.
+const char* choose_spec(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l, bool padded, Spec* first, Spec* fallback)
+{
+    const bool tn = l.b == HGEMM_COL_MAJOR;
+    const bool packed = l.lda == K && l.ldc == N && l.ldb == (tn ? K : N);
+    const char* source = "table";
+    if (!table_lookup(M, N, K, tn, first) || !packed) {
+        source = "model";
+        if (!model_choice(M, N, K, first, !tn)) {
+            *first = heuristic(M, N, K);
+            source = "rules";
+        }
+        *fallback = *first;
+        if (neighbour_choice(M, N, K, tn, *fallback, first)) return "neighbour";
+    }
+    if (tn || padded) first->tb = 0;      // B already has K contiguous / is copied once already
+    *fallback = *first;
+    return source;
+}
+
 hgemm_status_t init_blocked(hgemm_plan_s* p);
 
 hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, const char* spec_text,
@@ -797,18 +824,12 @@ hgemm_status_t init_plan(hgemm_plan_s* p, int64_t M, int64_t N, int64_t K, const
             p->spec = Spec();
             st = finish_plan(p);
         } else {
-            const bool packed = l.lda == K && l.ldc == N && l.ldb == (l.b == HGEMM_ROW_MAJOR ? N : K);
-            bool planned = false;
-            if (!table_lookup(M, N, K, l.b == HGEMM_COL_MAJOR, &p->spec) || !packed) {
-                if (!model_choice(M, N, K, &p->spec, l.b == HGEMM_ROW_MAJOR)) p->spec = heuristic(M, N, K);
-                const Spec model = p->spec;
-                if (neighbour_choice(M, N, K, l.b == HGEMM_COL_MAJOR, model, &p->spec)) {
-                    planned = finish_plan(p) == HGEMM_OK;
-                    if (!planned) p->spec = model;
-                }
+            Spec fallback;
+            if (!strcmp(choose_spec(M, N, K, l, p->padded, &p->spec, &fallback), "neighbour")) {
+                if (finish_plan(p) == HGEMM_OK) return HGEMM_OK;
+                p->spec = fallback;
+                if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;
             }
-            if (planned) return HGEMM_OK;
-            if (l.b == HGEMM_COL_MAJOR || p->padded) p->spec.tb = 0;      // B already has K contiguous / is copied once already
             st = finish_plan(p);
             if (st == HGEMM_ERR_UNSUPPORTED) {
                 // a table row naming a kernel this build lacks, or a row of the NN table, consulted for a
@@ -846,20 +867,20 @@ void destroy_blocks(hgemm_plan_s* p)
 
 // Plans a problem whose dimensions are aligned but whose operands reach 2 GiB as a grid of blocks (see
 // hgemm_plan_s).  On failure the plan is left as it was, for the generic kernel.
-hgemm_status_t init_blocked(hgemm_plan_s* p)
+// Block sizes for a problem whose dimensions are aligned but whose operands reach 2 GiB: rows per block of A and
+// C, columns per panel of B and C (equal sizes, multiples of 256), whether a row-major B has to go through a
+// transposed copy, and the layouts the blocks are planned for.  False when no such split exists.
+bool block_sizes(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t& l, int64_t* rows, int64_t* cols, bool* transposed, hgemm_layouts_t* block_lay)
 {
-    const int64_t M = p->M, N = p->N, K = p->K;
-    const hgemm_layouts_t l = p->lay;
     const int64_t lim = (int64_t)1 << 31;
     auto down256 = [](int64_t v) { return v / 256 * 256; };
     int64_t bm = std::min<int64_t>(M, std::min(down256((lim - 1) / (l.lda * 2) - 512), down256((((int64_t)1 << 33) - 1) / (l.ldc * 2))));
-    if (bm <= 0) return HGEMM_ERR_UNSUPPORTED;
+    if (bm <= 0) return false;
     hgemm_layouts_t sl = l;
     // can the matrix-core kernels address B as it lies?  (asked of a block of 256 rows)
-    hgemm_layouts_t probe = l;
     bool bt = false;
-    if (l.b == HGEMM_ROW_MAJOR && !fast_path_ok(std::min<int64_t>(bm, 256), N, K, probe)) {
-        if ((K + 63) / 64 > 65535) return HGEMM_ERR_UNSUPPORTED;          // grid of the transposing copy
+    if (l.b == HGEMM_ROW_MAJOR && !fast_path_ok(std::min<int64_t>(bm, 256), N, K, l)) {
+        if ((K + 63) / 64 > 65535) return false;          // grid of the transposing copy
         bt = true;
         sl.b = HGEMM_COL_MAJOR;
         sl.ldb = K;
@@ -867,7 +888,7 @@ hgemm_status_t init_blocked(hgemm_plan_s* p)
     int64_t bn = N;
     if (sl.b == HGEMM_COL_MAJOR) {
         bn = std::min<int64_t>(N, down256((lim - 1) / (sl.ldb * 2) - 512));
-        if (bn <= 0) return HGEMM_ERR_UNSUPPORTED;
+        if (bn <= 0) return false;
     }
     // blocks of equal size (a multiple of 256) rather than full ones and a sliver
     auto even = [](int64_t total, int64_t most) {
@@ -876,7 +897,21 @@ hgemm_status_t init_blocked(hgemm_plan_s* p)
     };
     if (bm < M) bm = even(M, bm);
     if (bn < N) bn = even(N, bn);
-    if (!fast_path_ok(bm, bn, K, sl)) return HGEMM_ERR_UNSUPPORTED;
+    if (!fast_path_ok(bm, bn, K, sl)) return false;
+    *rows = bm;
+    *cols = bn;
+    *transposed = bt;
+    *block_lay = sl;
+    return true;
+}
+
+hgemm_status_t init_blocked(hgemm_plan_s* p)
+{
+    const int64_t M = p->M, N = p->N, K = p->K;
+    int64_t bm = 0, bn = 0;
+    bool bt = false;
+    hgemm_layouts_t sl;
+    if (!block_sizes(M, N, K, p->lay, &bm, &bn, &bt, &sl)) return HGEMM_ERR_UNSUPPORTED;
     p->blocked_bt = bt;
     p->block_m = bm;
     p->block_n = bn;
@@ -944,6 +979,51 @@ hgemm_status_t hgemm_plan_override(hgemm_plan_t* out, int64_t M, int64_t N, int6
 {
     if (!spec) return HGEMM_ERR_INVALID_ARG;
     return make_plan(out, M, N, K, layouts, spec);
+}
+
+hgemm_status_t hgemm_plan_choice(int64_t M, int64_t N, int64_t K, const hgemm_layouts_t* layouts, char* buf, size_t n)
+{
+    if (!buf || n == 0 || M < 0 || N < 0 || K < 0) return HGEMM_ERR_INVALID_ARG;
+    hgemm_layouts_t l;
+    if (layouts) l = *layouts; else { l.a = l.b = l.c = HGEMM_ROW_MAJOR; l.lda = l.ldb = l.ldc = 0; }
+    if ((l.b != HGEMM_ROW_MAJOR && l.b != HGEMM_COL_MAJOR) || l.lda < 0 || l.ldb < 0 || l.ldc < 0) return HGEMM_ERR_INVALID_ARG;
+    if (l.a != HGEMM_ROW_MAJOR || l.c != HGEMM_ROW_MAJOR) return HGEMM_ERR_UNSUPPORTED;
+    if (l.lda == 0) l.lda = K;
+    if (l.ldb == 0) l.ldb = (l.b == HGEMM_ROW_MAJOR) ? N : K;
+    if (l.ldc == 0) l.ldc = N;
+    if (l.lda < K || l.ldc < N || l.ldb < ((l.b == HGEMM_ROW_MAJOR) ? N : K)) return HGEMM_ERR_INVALID_ARG;
+    std::string out;
+    const bool nonempty = M > 0 && N > 0 && K > 0;
+    bool fast = nonempty && fast_path_ok(M, N, K, l);
+    bool padded = false;
+    if (!fast && nonempty && (double)M * (double)N * (double)K >= kPadMinMacs) {
+        const int64_t Kp = (K + 7) / 8 * 8, Np = (N + 7) / 8 * 8;
+        hgemm_layouts_t lp = l;
+        lp.lda = Kp;
+        lp.ldb = (l.b == HGEMM_ROW_MAJOR) ? Np : Kp;
+        lp.ldc = Np;
+        if (fast_path_ok(M, Np, Kp, lp)) { padded = fast = true; N = Np; K = Kp; l = lp; }
+    }
+    int64_t rows = 0, cols = 0;
+    bool bt = false;
+    hgemm_layouts_t bl;
+    const bool dims_aligned = !(N % 8 || K % 8 || l.lda % 8 || l.ldb % 8 || l.ldc % 8) && M < (1 << 24) && N < (1 << 24) && K < (1 << 24);
+    if (!nonempty) {
+        out = "empty";
+    } else if (!fast && dims_aligned && block_sizes(M, N, K, l, &rows, &cols, &bt, &bl)) {
+        char head[96];
+        snprintf(head, sizeof head, "blocks,rows=%lld,cols=%lld%s", (long long)rows, (long long)cols, bt ? ",bt=1" : "");
+        out = head;
+    } else if (!fast) {
+        out = "generic";
+    } else {
+        Spec first, fallback;
+        const char* source = choose_spec(M, N, K, l, padded, &first, &fallback);
+        out = std::string(source) + ": " + spec_to_string(first) + (padded ? ",pad=1" : "");
+    }
+    if (out.size() + 1 > n) { buf[0] = '\0'; return HGEMM_ERR_INVALID_ARG; }
+    memcpy(buf, out.c_str(), out.size() + 1);
+    return HGEMM_OK;
 }
 
 static hgemm_status_t run_plan(const hgemm_plan_s* plan, const void* A, const void* B, void* C, void* hip_stream)

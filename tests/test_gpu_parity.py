@@ -557,6 +557,8 @@ def test_random_shapes_whatever_the_planner_picks_both_layouts():
         assert not np.isnan(c).any(), f"{shape} {desc}: part of C not written"
         assert np.isnan(before).all() and np.isnan(after).all(), f"{shape} {desc}: wrote outside C"
         seen.add("pad" if "pad=1" in desc else desc.split(",")[0])
+        # the host-only preview of the planner's decision names the plan that was set up
+        assert hg.plan_choice(M, N, K, hg.Layouts.make(b_col_major=tn)).split(": ")[-1] == desc, (shape, tn)
     assert {"mfma", "skinny", "generic", "pad"} <= seen, seen
 
 

@@ -117,3 +117,33 @@ def test_every_candidate_has_a_finite_positive_prediction(M, N8, K8):
     for s in cands[::3]:
         us = hg.predict_us(M, N, K, s)
         assert math.isfinite(us) and us > 1.0, (M, N, K, s, us)
+
+
+def test_plan_choice_names_the_source_of_every_kind_of_plan():
+    """hgemm_plan_choice is the planner's decision without a device: dispatch table, nearest tuned shape for large
+    problems off the table (unless its tiles fill the last round of workgroups worse than the model's pick),
+    cost model, streaming family for a few rows against weights no cache holds, padded copies, blocks for
+    operands of 2 GiB and more, generic kernel."""
+    import workloads as wl
+    tn = hg.Layouts.make(b_col_major=True)
+    for s in [wl.C1_SHAPE, *wl.C2_SHAPES, *wl.C3_SHAPES, *wl.C5_SHAPES, *wl.c4_shapes()[::7]]:
+        assert hg.plan_choice(*s).startswith("table: "), s
+        assert hg.plan_choice(*s, tn).startswith("table: mfma,"), s
+    assert hg.plan_choice(16, 28672, 8192) == "table: skinny,sk=1"
+    assert hg.plan_choice(16, 28672, 8192, tn).startswith("model: mfma,")        # the streaming family reads row-major B only
+    near = hg.plan_choice(3000, 5120, 5120)
+    assert near.startswith("neighbour: mfma,bm=256,bn=256,") and "mi=16" in near
+    assert hg.plan_choice(3000, 6144, 4096).startswith("model: mfma,bm=192,bn=192,")      # 512 tiles against the neighbour's 288
+    assert hg.plan_choice(4096, 4096, 4096, hg.Layouts.make(lda=4104)).startswith(("neighbour: ", "model: "))   # not packed: no table row
+    assert hg.plan_choice(8, 16384, 8192).startswith("model: skinny,")
+    assert hg.plan_choice(8, 4096, 4096).startswith("model: mfma,")
+    assert hg.plan_choice(300, 264, 128).startswith("model: mfma,")
+    assert hg.plan_choice(1000, 1001, 1003).endswith(",pad=1")
+    assert hg.plan_choice(100, 100, 100) == "generic" and hg.plan_choice(0, 5, 5) == "empty"
+    assert hg.plan_choice(32768, 32768, 32768) == "blocks,rows=16384,cols=16384,bt=1"
+    assert hg.plan_choice(32768, 32768, 32768, tn) == "blocks,rows=16384,cols=16384"
+    assert hg.plan_choice((1 << 21), 64, 1024) == "blocks,rows=699136,cols=64"
+    with pytest.raises(hg.HgemmError):
+        hg.plan_choice(-1, 8, 8)
+    with pytest.raises(hg.HgemmError):
+        hg.plan_choice(64, 64, 64, hg.Layouts.make(lda=8))
