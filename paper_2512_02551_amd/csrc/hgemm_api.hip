@@ -36,7 +36,7 @@ static const std::vector<MfmaEntry>& registry()
     return r;
 }
 
-void (*skinny_kernel(int mb, bool fused, int waves))(GemmArgs);      // hgemm_skinny.hip
+void (*skinny_kernel(int mb, bool fused, int waves, bool tn))(GemmArgs);      // hgemm_skinny.hip
 
 constexpr int64_t kSkinnyMaxM = 64;
 
@@ -57,8 +57,10 @@ struct Spec {
     int wv = 4;     // skinny family: waves per workgroup (4, 8 or 16), each taking 16 k-rows of a step
 };
 
-// k-rows a workgroup of the skinny family takes per step; K slabs are whole numbers of steps
-static int64_t skinny_step(const Spec& s) { return 16 * s.wv; }
+// k-rows a workgroup of the skinny family takes per step (K slabs are whole numbers of steps) and the columns of C
+// it owns: row-major B 16 rows per wave and 128 columns, column-major B 32 k per wave and 16 columns
+static int64_t skinny_step(const Spec& s, bool tn = false) { return (tn ? 32 : 16) * s.wv; }
+static int64_t skinny_cols(bool tn) { return tn ? kSkinnyTnRows : kSkinnyCols; }
 
 static std::string spec_to_string(const Spec& s)
 {
@@ -291,7 +293,7 @@ bool table_lookup(int64_t M, int64_t N, int64_t K, bool b_col_major, Spec* out)
         const DispatchRow& r = kDispatchTable[i];
         if (r.m == M && r.n == N && r.k == K) {
             // a row of the NN table serves a column-major B only if it names the large-tile family (the streaming
-            // family reads row-major B)
+            // family decomposes the two layouts differently: slab and wave counts do not carry over)
             return r.spec[0] != '\0' && parse_spec(r.spec, out) && !(b_col_major && out->fam != FAM_MFMA);
         }
     }
@@ -594,19 +596,20 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
     p->skinny = nullptr;
     if (s.fam == FAM_GENERIC) return HGEMM_OK;
     if (s.fam == FAM_SKINNY) {
-        // strips of 128 columns x K slabs of whole 64-row steps; partial planes as for split-K
-        if (p->lay.b != HGEMM_ROW_MAJOR || !fast_path_ok(M, N, K, p->lay) || M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM)
-            return HGEMM_ERR_UNSUPPORTED;
+        // strips of columns x K slabs of whole steps; partial planes as for split-K
+        if (!fast_path_ok(M, N, K, p->lay) || M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM) return HGEMM_ERR_UNSUPPORTED;
+        const bool tn = p->lay.b == HGEMM_COL_MAJOR;
+        p->tn_kernel = tn;
         const int mb = M <= 16 ? 1 : M <= 32 ? 2 : 4;
-        const int64_t step = skinny_step(s);
+        const int64_t step = skinny_step(s, tn);
         const int64_t ksteps = (K + step - 1) / step;
         const int64_t sk = effective_splits(ksteps, s.sk);
         if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
         s.sk = (int)sk;
         if (sk == 1) s.fr = 0;
-        const int64_t strips = (N + kSkinnyCols - 1) / kSkinnyCols;
+        const int64_t strips = (N + skinny_cols(tn) - 1) / skinny_cols(tn);
         if (s.fr && strips * (int64_t)sizeof(int) > (int64_t)kCounterBytes) return HGEMM_ERR_UNSUPPORTED;
-        p->skinny = skinny_kernel(mb, s.fr != 0, s.wv);
+        p->skinny = skinny_kernel(mb, s.fr != 0, s.wv, tn);
         if (!p->skinny) return HGEMM_ERR_UNSUPPORTED;
         GemmArgs& a = p->args;
         a.M = (int)M; a.N = (int)N; a.K = (int)K;
@@ -1258,7 +1261,7 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
     int64_t wg, lds, th;
     if (plan->skinny) {
         wg = (int64_t)plan->args.tiles_n * plan->args.splits;
-        lds = 4 * 16 * (kSkinnyCols + 4) * 4;
+        lds = plan->tn_kernel ? plan->spec.wv * (plan->M <= 16 ? 1 : plan->M <= 32 ? 2 : 4) * 1024 : 4 * 16 * (kSkinnyCols + 4) * 4;
         th = 64 * plan->spec.wv;
     } else if (plan->entry) {
         wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
@@ -1289,7 +1292,10 @@ const char* hgemm_spec_help(void)
             "    take 128 columns and a K slab each and stream it in steps of 16 * wv rows; a wave takes 16 rows of a\n"
             "    step, transposes its 4 x 8 blocks in registers for 16x16x16 matrix-core instructions (M on a 16-wide\n"
             "    side; no LDS and no barrier in the main loop), the waves' sums meet once at the end; slabs are summed in\n"
-            "    slab order by the split-K reduction launch or, with fr = 1, by the workgroup that arrives last\n"
+            "    slab order by the split-K reduction launch or, with fr = 1, by the workgroup that arrives last.\n"
+            "    Column-major B (K contiguous): a workgroup takes 16 rows of B (16 columns of C), its waves split its K\n"
+            "    range into contiguous parts of whole 32-k steps, 16-byte loads are the operands of 16x16x32 instructions\n"
+            "    as they come; sk splits K further across workgroups\n"
             "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16][,mi=16]\n"
             "    pipelined 32x32x16 MFMA kernel; BMxBN tile per workgroup, WMxWN wavefronts, STAGES LDS buffers,\n"
             "    pf = register prefetch distance in k-steps (1 = ping-pong, 3 = four fragment sets),\n"
@@ -1360,6 +1366,24 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
                         Spec s;
                         s.fam = FAM_SKINNY; s.sk = (int)eff; s.fr = fr; s.wv = wv;
                         if (effective_splits((K + skinny_step(s) - 1) / skinny_step(s), eff) != eff) continue;
+                        out += spec_to_string(s);
+                        out += "\n";
+                    }
+                }
+            }
+        }
+        if (l.b == HGEMM_COL_MAJOR && M <= kSkinnyMaxM) {       // the streaming family for K-contiguous B: N / 16 workgroups before any split
+            for (int wv : {4, 8, 16}) {
+                if (wv == 16 && M > 32) continue;
+                int64_t last = 0;
+                for (int sk : {1, 2, 4, 8, 16}) {
+                    Spec s;
+                    s.fam = FAM_SKINNY; s.wv = wv;
+                    const int64_t eff = effective_splits((K + skinny_step(s, true) - 1) / skinny_step(s, true), sk);
+                    if (eff == last || ((N + kSkinnyTnRows - 1) / kSkinnyTnRows) * eff > 64 * CUS) continue;
+                    last = eff;
+                    for (int fr = 0; fr <= (eff > 1 ? 1 : 0); ++fr) {
+                        s.sk = (int)eff; s.fr = fr;
                         out += spec_to_string(s);
                         out += "\n";
                     }

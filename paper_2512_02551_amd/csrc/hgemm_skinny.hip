@@ -22,16 +22,30 @@ void (*kernel_for(int mb, bool fused))(GemmArgs)
     }
     return nullptr;
 }
+
+template <int WAVES>
+void (*tn_kernel_for(int mb, bool fused))(GemmArgs)
+{
+    // loads in flight per lane: 8 steps of 16 bytes of B (and of every 16-row block of A) for one block, 4 for more
+    switch (mb) {
+        case 1: return fused ? skinny_tn_gemm_kernel<1, true, 8, WAVES> : skinny_tn_gemm_kernel<1, false, 8, WAVES>;
+        case 2: return fused ? skinny_tn_gemm_kernel<2, true, 4, WAVES> : skinny_tn_gemm_kernel<2, false, 4, WAVES>;
+        case 4:
+            if constexpr (WAVES < 16) return fused ? skinny_tn_gemm_kernel<4, true, 4, WAVES> : skinny_tn_gemm_kernel<4, false, 4, WAVES>;
+            break;
+    }
+    return nullptr;
+}
 }  // namespace
 
 // Kernel for M <= 16 * mb (mb in {1, 2, 4}) and workgroups of 4, 8 or 16 waves, with or without the fused
-// reduction; null for other values.
-void (*skinny_kernel(int mb, bool fused, int waves))(GemmArgs)
+// reduction, for row-major B (tn = false) or column-major B; null for other values.
+void (*skinny_kernel(int mb, bool fused, int waves, bool tn))(GemmArgs)
 {
     switch (waves) {
-        case 4: return kernel_for<4>(mb, fused);
-        case 8: return kernel_for<8>(mb, fused);
-        case 16: return kernel_for<16>(mb, fused);
+        case 4: return tn ? tn_kernel_for<4>(mb, fused) : kernel_for<4>(mb, fused);
+        case 8: return tn ? tn_kernel_for<8>(mb, fused) : kernel_for<8>(mb, fused);
+        case 16: return tn ? tn_kernel_for<16>(mb, fused) : kernel_for<16>(mb, fused);
     }
     return nullptr;
 }

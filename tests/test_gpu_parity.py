@@ -394,6 +394,23 @@ def test_skinny_family_every_spec_bit_exact(shape):
     two, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=2,wv=8")
     one, _, _, _ = run_hgemm(ar, br, spec="skinny,sk=2,fr=1,wv=8")
     assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    # column-major B: 16 columns of C per workgroup, the waves split K, 16-byte loads are the matrix-core operands
+    tn = hg.Layouts.make(b_col_major=True)
+    bt, brt = np.ascontiguousarray(b.T), np.ascontiguousarray(br.T)
+    tn_specs = [c for c in hg.candidates(*shape, tn) if c.startswith("skinny")]
+    assert tn_specs and any("wv=8" in x for x in tn_specs)
+    for spec in tn_specs + ["skinny,sk=3", "skinny,sk=2,fr=1,wv=8"]:
+        c, before, after, desc = run_hgemm(a, bt, spec=spec, b_col_major=True, guard=3)
+        assert desc.startswith("skinny")
+        assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
+        assert np.isnan(before).all() and np.isnan(after).all(), f"TN {desc}: wrote outside C"
+        c, _, _, _ = run_hgemm(ar, brt, spec=spec, b_col_major=True)
+        assert_close(c, refr, f"TN {shape} real {desc}")
+        again, _, _, _ = run_hgemm(ar, brt, spec=spec, b_col_major=True)
+        assert np.array_equal(c.view(np.uint16), again.view(np.uint16)), f"TN {desc}: two runs differ"
+    two, _, _, _ = run_hgemm(ar, brt, spec="skinny,sk=2,wv=8", b_col_major=True)
+    one, _, _, _ = run_hgemm(ar, brt, spec="skinny,sk=2,fr=1,wv=8", b_col_major=True)
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
 
 
 def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals():
@@ -415,11 +432,11 @@ def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals(
                 out = to_host(C)
                 assert_bit_exact(out[:, :N], ref, f"{spec} launch {rep}")
                 assert np.isnan(out[:, N:]).all(), spec
-    # column-major B, unaligned shapes and tall A are not this family's
-    with pytest.raises(hg.HgemmError):
-        hg.Plan(8, 64, 64, hg.Layouts.make(b_col_major=True), "skinny,sk=1")
+    # unaligned shapes and tall A are not this family's
     with pytest.raises(hg.HgemmError):
         hg.Plan(8, 60, 64, None, "skinny,sk=1")
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(64, 64, 64, hg.Layouts.make(b_col_major=True), "skinny,sk=1,wv=16")
     with pytest.raises(hg.HgemmError):
         hg.Plan(65, 64, 64, None, "skinny,sk=1")
     with pytest.raises(hg.HgemmError):
@@ -445,10 +462,11 @@ def test_skinny_family_non_finite_and_subnormal_values(spec):
     b[17, 130] = np.inf       # a whole column of +-inf or, where A[m][17] == 0, NaN: column 130 only
     b[199, 263] = np.nan
     ref = orc.hgemm(a, b)
-    c, _, _, desc = run_hgemm(a, b, spec=spec)
-    assert np.array_equal(np.isnan(c), np.isnan(ref)), desc
-    fin = ~np.isnan(ref)
-    assert np.array_equal(c[fin].astype(np.float64), ref[fin].astype(np.float64)), desc
+    for tn in (False, True):
+        c, _, _, desc = run_hgemm(a, np.ascontiguousarray(b.T) if tn else b, spec=spec, b_col_major=tn)
+        assert np.array_equal(np.isnan(c), np.isnan(ref)), desc
+        fin = ~np.isnan(ref)
+        assert np.array_equal(c[fin].astype(np.float64), ref[fin].astype(np.float64)), desc
     clean = [m for m in range(M) if m not in (3, 10)]          # rows of A without a non-finite value
     assert np.isfinite(ref[clean, 129]).all() and np.isfinite(ref[clean, 131]).all() and not np.isfinite(ref[:, 130]).any()
     rng = np.random.default_rng(78)
