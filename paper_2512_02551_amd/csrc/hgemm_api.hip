@@ -36,7 +36,7 @@ static const std::vector<MfmaEntry>& registry()
     return r;
 }
 
-void (*skinny_kernel(int mb, bool fused, int waves, bool tn))(GemmArgs);      // hgemm_skinny.hip
+void (*skinny_kernel(int mb, bool fused, int waves, int tn_rows))(GemmArgs);      // hgemm_skinny.hip
 
 constexpr int64_t kSkinnyMaxM = 64;
 
@@ -55,12 +55,13 @@ struct Spec {
     int ac = 32;    // accumulator width: 32 = fp32 over all of K; 16 = rounded to fp16 after every 16 products
     int mi = 32;    // matrix-core output block: 32 = v_mfma_f32_32x32x16_f16, 16 = v_mfma_f32_16x16x32_f16
     int wv = 4;     // skinny family: waves per workgroup (4, 8 or 16), each taking 16 k-rows of a step
+    int nr = 16;    // skinny family, column-major B: rows of B (columns of C) per workgroup (16, 32 or 64)
 };
 
 // k-rows a workgroup of the skinny family takes per step (K slabs are whole numbers of steps) and the columns of C
 // it owns: row-major B 16 rows per wave and 128 columns, column-major B 32 k per wave and 16 columns
 static int64_t skinny_step(const Spec& s, bool tn = false) { return (tn ? 32 : 16) * s.wv; }
-static int64_t skinny_cols(bool tn) { return tn ? kSkinnyTnRows : kSkinnyCols; }
+static int64_t skinny_cols(const Spec& s, bool tn) { return tn ? s.nr : kSkinnyCols; }
 
 static std::string spec_to_string(const Spec& s)
 {
@@ -69,6 +70,7 @@ static std::string spec_to_string(const Spec& s)
     if (s.fam == FAM_SKINNY) {
         snprintf(buf, sizeof buf, "skinny,sk=%d%s", s.sk, s.fr ? ",fr=1" : "");
         if (s.wv != 4) snprintf(buf + strlen(buf), sizeof buf - strlen(buf), ",wv=%d", s.wv);
+        if (s.nr != 16) snprintf(buf + strlen(buf), sizeof buf - strlen(buf), ",nr=%d", s.nr);
         return buf;
     }
     snprintf(buf, sizeof buf, "mfma,bm=%d,bn=%d,bk=%d,wm=%d,wn=%d,st=%d,pf=%d,sk=%d,gm=%d%s", s.bm, s.bn, s.bk, s.wm, s.wn,
@@ -123,6 +125,7 @@ static bool parse_spec(const char* text, Spec* out)
         else if (key == "ac") sp.ac = (int)v;
         else if (key == "mi") sp.mi = (int)v;
         else if (key == "wv") sp.wv = (int)v;
+        else if (key == "nr") sp.nr = (int)v;
         else if (key == "pad") { /* reported by hgemm_plan_describe; padding follows from the shape, not from the spec */ }
         else return false;
     }
@@ -132,6 +135,7 @@ static bool parse_spec(const char* text, Spec* out)
     if ((sp.ac != 32 && sp.ac != 16) || (sp.ac == 16 && (sp.fam != FAM_MFMA || sp.sk > 1 || sp.sm || sp.ps || sp.fr))) return false;
     if (sp.mi != 32 && sp.mi != 16) return false;
     if ((sp.wv != 4 && sp.wv != 8 && sp.wv != 16) || (sp.wv != 4 && sp.fam != FAM_SKINNY)) return false;
+    if ((sp.nr != 16 && sp.nr != 32 && sp.nr != 64) || (sp.nr != 16 && sp.fam != FAM_SKINNY)) return false;
     *out = sp;
     return true;
 }
@@ -607,9 +611,10 @@ hgemm_status_t finish_plan(hgemm_plan_s* p)
         if (sk > 65535) return HGEMM_ERR_UNSUPPORTED;
         s.sk = (int)sk;
         if (sk == 1) s.fr = 0;
-        const int64_t strips = (N + skinny_cols(tn) - 1) / skinny_cols(tn);
+        if (!tn && s.nr != 16) return HGEMM_ERR_UNSUPPORTED;
+        const int64_t strips = (N + skinny_cols(s, tn) - 1) / skinny_cols(s, tn);
         if (s.fr && strips * (int64_t)sizeof(int) > (int64_t)kCounterBytes) return HGEMM_ERR_UNSUPPORTED;
-        p->skinny = skinny_kernel(mb, s.fr != 0, s.wv, tn);
+        p->skinny = skinny_kernel(mb, s.fr != 0, s.wv, tn ? s.nr : 0);
         if (!p->skinny) return HGEMM_ERR_UNSUPPORTED;
         GemmArgs& a = p->args;
         a.M = (int)M; a.N = (int)N; a.K = (int)K;
@@ -1261,7 +1266,7 @@ hgemm_status_t hgemm_plan_launch_info(hgemm_plan_t plan, int64_t* workgroups, in
     int64_t wg, lds, th;
     if (plan->skinny) {
         wg = (int64_t)plan->args.tiles_n * plan->args.splits;
-        lds = plan->tn_kernel ? plan->spec.wv * (plan->M <= 16 ? 1 : plan->M <= 32 ? 2 : 4) * 1024 : 4 * 16 * (kSkinnyCols + 4) * 4;
+        lds = plan->tn_kernel ? plan->spec.wv * (plan->M <= 16 ? 1 : plan->M <= 32 ? 2 : 4) * (plan->spec.nr / 16) * 1024 : 4 * 16 * (kSkinnyCols + 4) * 4;
         th = 64 * plan->spec.wv;
     } else if (plan->entry) {
         wg = plan->spec.sm ? (int64_t)plan->args.dp_tiles + plan->args.sk_workers
@@ -1287,13 +1292,13 @@ const char* hgemm_spec_help(void)
         std::string t =
             "generic\n"
             "    one thread per element, any shape, alignment and layout\n"
-            "skinny,sk=SPLITS[,fr=1][,wv=WAVES]\n"
+            "skinny,sk=SPLITS[,fr=1][,wv=WAVES][,nr=ROWS]\n"
             "    memory-bound kernel for M <= 64 rows of A (row-major B): workgroups of wv = 4 (default), 8 or 16 waves\n"
             "    take 128 columns and a K slab each and stream it in steps of 16 * wv rows; a wave takes 16 rows of a\n"
             "    step, transposes its 4 x 8 blocks in registers for 16x16x16 matrix-core instructions (M on a 16-wide\n"
             "    side; no LDS and no barrier in the main loop), the waves' sums meet once at the end; slabs are summed in\n"
             "    slab order by the split-K reduction launch or, with fr = 1, by the workgroup that arrives last.\n"
-            "    Column-major B (K contiguous): a workgroup takes 16 rows of B (16 columns of C), its waves split its K\n"
+            "    Column-major B (K contiguous): a workgroup takes nr = 16 (default), 32 or 64 rows of B (columns of C), its waves split its K\n"
             "    range into contiguous parts of whole 32-k steps, 16-byte loads are the operands of 16x16x32 instructions\n"
             "    as they come; sk splits K further across workgroups\n"
             "mfma,bm=BM,bn=BN,bk=BK,wm=WM,wn=WN,st=STAGES[,pf=PREFETCH][,sk=SPLITS][,gm=GROUP][,tb=1][,sm=1][,fr=1][,ps=1][,ac=16][,mi=16]\n"
@@ -1373,22 +1378,26 @@ hgemm_status_t hgemm_candidates(int64_t M, int64_t N, int64_t K, const hgemm_lay
             }
         }
         if (l.b == HGEMM_COL_MAJOR && M <= kSkinnyMaxM) {       // the streaming family for K-contiguous B: N / 16 workgroups before any split
-            for (int wv : {4, 8, 16}) {
-                if (wv == 16 && M > 32) continue;
-                int64_t last = 0;
-                for (int sk : {1, 2, 4, 8, 16}) {
-                    Spec s;
-                    s.fam = FAM_SKINNY; s.wv = wv;
-                    const int64_t eff = effective_splits((K + skinny_step(s, true) - 1) / skinny_step(s, true), sk);
-                    if (eff == last || ((N + kSkinnyTnRows - 1) / kSkinnyTnRows) * eff > 64 * CUS) continue;
-                    last = eff;
-                    for (int fr = 0; fr <= (eff > 1 ? 1 : 0); ++fr) {
-                        s.sk = (int)eff; s.fr = fr;
-                        out += spec_to_string(s);
-                        out += "\n";
+            const int mblocks = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+            for (int nr : {16, 32, 64})
+                for (int wv : {4, 8, 16}) {
+                    const int blocks = mblocks * (nr / 16);
+                    if (wv * blocks > 64 || (wv == 16 && blocks > 4)) continue;       // kernels that do not exist
+                    if (nr > 16 && (N + nr - 1) / nr < CUS / 2) continue;             // too few workgroups to be worth timing
+                    int64_t last = 0;
+                    for (int sk : {1, 2, 4, 8, 16}) {
+                        Spec s;
+                        s.fam = FAM_SKINNY; s.wv = wv; s.nr = nr;
+                        const int64_t eff = effective_splits((K + skinny_step(s, true) - 1) / skinny_step(s, true), sk);
+                        if (eff == last || ((N + nr - 1) / nr) * eff > 64 * CUS) continue;
+                        last = eff;
+                        for (int fr = 0; fr <= (eff > 1 ? 1 : 0); ++fr) {
+                            s.sk = (int)eff; s.fr = fr;
+                            out += spec_to_string(s);
+                            out += "\n";
+                        }
                     }
                 }
-            }
         }
         for (const MfmaEntry& e : registry()) {
             if (!tile_fits_problem(e, M, N)) continue;

@@ -23,29 +23,47 @@ void (*kernel_for(int mb, bool fused))(GemmArgs)
     return nullptr;
 }
 
-template <int WAVES>
-void (*tn_kernel_for(int mb, bool fused))(GemmArgs)
+// Column-major B.  Steps of loads in flight per lane: 16 registers' worth of 16-byte loads shared between the NR / 16
+// blocks of B and the MB blocks of A of a step, at least 2, at most 8.  Combinations whose sums would not fit 64 KiB
+// of LDS, or whose accumulators and loads would not fit the 128 registers a 16-wave workgroup leaves a lane, do not exist.
+template <int WAVES, int MB, int NR>
+void (*tn_kernel(bool fused))(GemmArgs)
 {
-    // loads in flight per lane: 8 steps of 16 bytes of B (and of every 16-row block of A) for one block, 4 for more
-    switch (mb) {
-        case 1: return fused ? skinny_tn_gemm_kernel<1, true, 8, WAVES> : skinny_tn_gemm_kernel<1, false, 8, WAVES>;
-        case 2: return fused ? skinny_tn_gemm_kernel<2, true, 4, WAVES> : skinny_tn_gemm_kernel<2, false, 4, WAVES>;
-        case 4:
-            if constexpr (WAVES < 16) return fused ? skinny_tn_gemm_kernel<4, true, 4, WAVES> : skinny_tn_gemm_kernel<4, false, 4, WAVES>;
-            break;
+    constexpr int NB = NR / 16;
+    constexpr int DEPTH = 16 / (NB + MB) < 2 ? 2 : 16 / (NB + MB) > 8 ? 8 : 16 / (NB + MB);
+    if constexpr (WAVES * MB * NB <= 64 && (WAVES < 16 || MB * NB <= 4))
+        return fused ? skinny_tn_gemm_kernel<MB, true, DEPTH, WAVES, NR> : skinny_tn_gemm_kernel<MB, false, DEPTH, WAVES, NR>;
+    else
+        return nullptr;
+}
+
+template <int WAVES>
+void (*tn_kernel_for(int mb, bool fused, int nr))(GemmArgs)
+{
+    switch (mb * 100 + nr) {
+        case 116: return tn_kernel<WAVES, 1, 16>(fused);
+        case 132: return tn_kernel<WAVES, 1, 32>(fused);
+        case 164: return tn_kernel<WAVES, 1, 64>(fused);
+        case 216: return tn_kernel<WAVES, 2, 16>(fused);
+        case 232: return tn_kernel<WAVES, 2, 32>(fused);
+        case 264: return tn_kernel<WAVES, 2, 64>(fused);
+        case 416: return tn_kernel<WAVES, 4, 16>(fused);
+        case 432: return tn_kernel<WAVES, 4, 32>(fused);
+        case 464: return tn_kernel<WAVES, 4, 64>(fused);
     }
     return nullptr;
 }
 }  // namespace
 
 // Kernel for M <= 16 * mb (mb in {1, 2, 4}) and workgroups of 4, 8 or 16 waves, with or without the fused
-// reduction, for row-major B (tn = false) or column-major B; null for other values.
-void (*skinny_kernel(int mb, bool fused, int waves, bool tn))(GemmArgs)
+// reduction, for row-major B (tn_rows = 0) or column-major B with tn_rows = 16, 32 or 64 rows of B per workgroup;
+// null for other values.
+void (*skinny_kernel(int mb, bool fused, int waves, int tn_rows))(GemmArgs)
 {
     switch (waves) {
-        case 4: return tn ? tn_kernel_for<4>(mb, fused) : kernel_for<4>(mb, fused);
-        case 8: return tn ? tn_kernel_for<8>(mb, fused) : kernel_for<8>(mb, fused);
-        case 16: return tn ? tn_kernel_for<16>(mb, fused) : kernel_for<16>(mb, fused);
+        case 4: return tn_rows ? tn_kernel_for<4>(mb, fused, tn_rows) : kernel_for<4>(mb, fused);
+        case 8: return tn_rows ? tn_kernel_for<8>(mb, fused, tn_rows) : kernel_for<8>(mb, fused);
+        case 16: return tn_rows ? tn_kernel_for<16>(mb, fused, tn_rows) : kernel_for<16>(mb, fused);
     }
     return nullptr;
 }

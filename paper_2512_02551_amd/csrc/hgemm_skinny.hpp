@@ -207,23 +207,28 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(GemmArgs g)
 
 // The same family for column-major B (stored N x K, K contiguous: the layout in which frameworks keep the
 // weights of a linear layer).  Here nothing needs transposing: v_mfma_f32_16x16x32_f16 takes 8 consecutive k
-// per lane, and a 16-byte load of row n of B is exactly that.  A workgroup owns 16 rows of B (16 columns of
-// C), so N / 16 workgroups exist before K is split at all; its WAVES waves split the workgroup's K range
-// into contiguous parts (every row is read in runs of kilobytes), each wave keeps DEPTH loads of 1 KiB in
-// flight, holds 4 accumulator registers per 16-row block of A, and the waves' sums meet in LDS at the end and
-// are added in wave order.  grid.y splits K further (planes, reduction launch or FUSED) for short, wide-K problems.
-constexpr int kSkinnyTnRows = 16;      // rows of B (columns of C) per workgroup
+// per lane, and a 16-byte load of row n of B is exactly that.  A workgroup owns NR = 16, 32 or 64 rows of B (as
+// many columns of C), so N / NR workgroups exist before K is split at all; its WAVES waves split the
+// workgroup's K range into contiguous parts (every row is read in runs of kilobytes), each wave keeps DEPTH
+// steps of loads in flight (NR / 16 KiB of B each), holds 4 accumulator registers per 16 x 16 block of C, and
+// the waves' sums meet in LDS at the end and are added in wave order.  Every workgroup reads the rows of A it
+// multiplies once per NR rows of B: at NR = 16 and M = 16 that is as many bytes through the L1s again as B
+// itself, which is what the wider workgroups are for.  grid.y splits K further (planes, reduction launch or
+// FUSED) for short, wide-K problems.
+constexpr int kSkinnyTnRows = 16;      // rows of B (columns of C) per workgroup unless a spec asks for more
 
-template <int MB, bool FUSED, int DEPTH, int WAVES>
+template <int MB, bool FUSED, int DEPTH, int WAVES, int NR>
 __global__ __launch_bounds__(64 * WAVES) void skinny_tn_gemm_kernel(GemmArgs g)
 {
     typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-    __shared__ __attribute__((aligned(16))) float red[WAVES * MB * 64 * 4];
+    constexpr int NB = NR / 16;                                // 16-row blocks of B per workgroup
+    static_assert(NR % 16 == 0 && WAVES * MB * NB <= 64, "the waves' sums meet in at most 64 KiB of LDS");
+    __shared__ __attribute__((aligned(16))) float red[WAVES * MB * NB * 64 * 4];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int n0 = blockIdx.x * kSkinnyTnRows;
+    const int n0 = blockIdx.x * NR;
     const int split = blockIdx.y;
     const int k_lo = split * g.k_per_split;
     const int k_hi = min(g.K, k_lo + g.k_per_split);
@@ -238,30 +243,38 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_tn_gemm_kernel(GemmArgs g)
     const __amdgpu_buffer_rsrc_t rsrcB =
         __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, (int)min((long long)g.N * g.ldb * 2, 0x7fffffffLL), 0x00020000);
 
-    // lane (grp, c16): B row n0 + c16 and A row 16 mb + c16, k = kw + 32 step + 8 grp .. + 7 (K is a multiple of 8:
-    // the eight k of a lane are in range together or not at all)
+    // lane (grp, c16): B rows n0 + 16 nb + c16 and A rows 16 mb + c16, k = kw + 32 step + 8 grp .. + 7 (K is a
+    // multiple of 8: the eight k of a lane are in range together or not at all)
     const int c16 = lane & 15, grp = lane >> 4;
     const int k0 = kw + 8 * grp;
-    const unsigned b_off = n0 + c16 < g.N ? (unsigned)(((n0 + c16) * g.ldb + k0) * 2) : OOB;
-    unsigned a_off[MB];
+    unsigned b_off[NB], a_off[MB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int n = n0 + 16 * nb + c16;
+        b_off[nb] = n < g.N ? (unsigned)((n * g.ldb + k0) * 2) : OOB;
+    }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = 16 * mb + c16;
         a_off[mb] = m < g.M ? (unsigned)((m * g.lda + k0) * 2) : OOB;
     }
-    auto load_step = [&](int step, uint4v& b, uint4v (&a)[MB]) {
+    auto load_step = [&](int step, uint4v (&b)[NB], uint4v (&a)[MB]) {
         const bool ok = k0 + 32 * step < kw_hi;
-        b = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, ok && b_off != OOB ? b_off + (unsigned)(step * 64) : OOB, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            b[nb] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, ok && b_off[nb] != OOB ? b_off[nb] + (unsigned)(step * 64) : OOB, 0, 0);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
             a[mb] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, ok && a_off[mb] != OOB ? a_off[mb] + (unsigned)(step * 64) : OOB, 0, 0);
     };
 
-    float4v acc[MB];
+    float4v acc[MB][NB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[mb] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    uint4v bq[DEPTH];
+    uint4v bq[DEPTH][NB];
     uint4v fa[DEPTH][MB];
 #pragma unroll
     for (int u = 0; u < DEPTH; ++u) load_step(u, bq[u], fa[u]);
@@ -270,28 +283,37 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_tn_gemm_kernel(GemmArgs g)
         for (int u = 0; u < DEPTH; ++u) {
             const int step = base + u;
             if (step >= steps) break;
-            union { uint4v i; half8 h; } bv, av[MB];
-            bv.i = bq[u];
+            union { uint4v i; half8 h; } bv[NB], av[MB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) bv[nb].i = bq[u][nb];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) av[mb].i = fa[u][mb];
             load_step(step + DEPTH, bq[u], fa[u]);           // refill this set
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bv.h, av[mb].h, acc[mb], 0, 0, 0);
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bv[nb].h, av[mb].h, acc[mb][nb], 0, 0, 0);
         }
     }
 
-    // ---- the waves' sums meet in LDS.  acc[mb][r] belongs to C[16 mb + c16][n0 + 4 grp + r]
+    // ---- the waves' sums meet in LDS.  acc[mb][nb][r] belongs to C[16 mb + c16][n0 + 16 nb + 4 grp + r]
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) *(float4v*)(red + ((wave * MB + mb) * 64 + lane) * 4) = acc[mb];
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) *(float4v*)(red + (((wave * MB + mb) * NB + nb) * 64 + lane) * 4) = acc[mb][nb];
     __syncthreads();
     const bool direct = g.splits == 1;
-    if (t < 64) {
+    // block (mb, nb) is summed by wave (mb * NB + nb) % WAVES
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            if ((mb * NB + nb) % WAVES != wave) continue;
             float4v s = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) s += *(const float4v*)(red + ((w * MB + mb) * 64 + lane) * 4);
-            const int m = 16 * mb + c16, n = n0 + 4 * grp;
+            for (int w = 0; w < WAVES; ++w) s += *(const float4v*)(red + (((w * MB + mb) * NB + nb) * 64 + lane) * 4);
+            const int m = 16 * mb + c16, n = n0 + 16 * nb + 4 * grp;
             if (m >= g.M || n >= g.N) continue;
             if (direct) {
                 half4 o;
@@ -313,7 +335,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_tn_gemm_kernel(GemmArgs g)
     }
     if (!FUSED || direct) return;
 
-    // fused reduction over the K slabs of these 16 columns, as in skinny_gemm_kernel
+    // fused reduction over the K slabs of these columns, as in skinny_gemm_kernel
     __syncthreads();
     int* flag = (int*)red;
     if (t == 0) {
@@ -324,8 +346,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_tn_gemm_kernel(GemmArgs g)
     }
     __syncthreads();
     if (*flag != g.splits - 1) return;
-    sum_split_planes<64 * WAVES, kSkinnyTnRows / 4>(g, 0, n0, g.M, t);
+    sum_split_planes<64 * WAVES, NR / 4>(g, 0, n0, g.M, t);
 }
-
 
 }  // namespace hgemm

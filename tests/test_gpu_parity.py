@@ -399,7 +399,8 @@ def test_skinny_family_every_spec_bit_exact(shape):
     bt, brt = np.ascontiguousarray(b.T), np.ascontiguousarray(br.T)
     tn_specs = [c for c in hg.candidates(*shape, tn) if c.startswith("skinny")]
     assert tn_specs and any("wv=8" in x for x in tn_specs)
-    for spec in tn_specs + ["skinny,sk=3", "skinny,sk=2,fr=1,wv=8"]:
+    # wider workgroups (32 or 64 rows of B) are candidates only for wide N: named here
+    for spec in tn_specs + ["skinny,sk=3", "skinny,sk=2,fr=1,wv=8", "skinny,sk=1,nr=32", "skinny,sk=3,nr=64", "skinny,sk=2,fr=1,wv=8,nr=32"]:
         c, before, after, desc = run_hgemm(a, bt, spec=spec, b_col_major=True, guard=3)
         assert desc.startswith("skinny")
         assert_bit_exact(c, ref, f"TN {shape} {name} {desc}")
@@ -436,7 +437,9 @@ def test_skinny_family_repeated_launches_padded_leading_dimensions_and_refusals(
     with pytest.raises(hg.HgemmError):
         hg.Plan(8, 60, 64, None, "skinny,sk=1")
     with pytest.raises(hg.HgemmError):
-        hg.Plan(64, 64, 64, hg.Layouts.make(b_col_major=True), "skinny,sk=1,wv=16")
+        hg.Plan(64, 64, 64, hg.Layouts.make(b_col_major=True), "skinny,sk=1,wv=8,nr=64")      # sums beyond 64 KiB of LDS
+    with pytest.raises(hg.HgemmError):
+        hg.Plan(16, 64, 64, None, "skinny,sk=1,nr=32")                                       # row-major B has 128-column strips
     with pytest.raises(hg.HgemmError):
         hg.Plan(65, 64, 64, None, "skinny,sk=1")
     with pytest.raises(hg.HgemmError):
