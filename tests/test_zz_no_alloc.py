@@ -76,6 +76,23 @@ def test_static_entry_point_tn_layout_and_degenerate_sizes():
     hg.run_static(8, 0, 8, None, 0, 0, 0, torch.cuda.current_stream().cuda_stream)
 
 
+def test_static_entry_point_on_rows_of_the_streaming_family():
+    # table rows that name the streaming family: fused reduction (arrival counters in the scratch, which must come
+    # back to zero for the next call), two-launch reduction (planes in the scratch), and the column-major kernel
+    for (shape, tn) in [((1, 8192, 8192), False), ((16, 8192, 8192), False), ((1, 8192, 8192), False), ((1, 4096, 4096), True)]:
+        M, N, K = shape
+        assert hg.plan_choice(M, N, K, hg.Layouts.make(b_col_major=tn)).startswith("table: skinny,")
+        name, a, b = wl.exact_family_for(shape, seed=43)
+        bb = np.ascontiguousarray(b.T) if tn else b
+        want, _, _, desc = run_hgemm(a, bb, b_col_major=tn)
+        assert desc.startswith("skinny,")
+        assert_bit_exact(_run_static(a, bb, b_col_major=tn), want, f"static {shape} {name} {desc}")
+        ii, jj = wl.sample_positions(shape, 1000, seed=7)
+        ref = orc.hgemm_at(a, b, ii, jj)
+        sel = np.abs(ref.astype(np.float64)) <= 2048
+        assert np.array_equal(want[ii, jj][sel].astype(np.float64), ref[sel].astype(np.float64)), desc
+
+
 def test_static_entry_point_refuses_what_does_not_fit():
     # a split-K plan whose planes exceed the static scratch: refused with a status of its own, nothing launched
     M, N, K = 2048, 2048, 16384
