@@ -131,8 +131,7 @@ def test_plan_choice_names_the_source_of_every_kind_of_plan():
         assert hg.plan_choice(*s, tn).startswith("table: "), s
     assert hg.plan_choice(16, 28672, 8192) == "table: skinny,sk=1"
     assert hg.plan_choice(1, 4096, 4096, tn).startswith("table: skinny,")        # column-major B has streaming rows of its own
-    # ... and never borrows one from the NN table: slab and wave counts do not carry over between the layouts
-    assert hg.plan_choice(1, 15360, 5120).startswith("table: skinny,") and hg.plan_choice(1, 15360, 5120, tn).startswith("model: mfma,")
+    assert hg.plan_choice(1, 15360, 5120).startswith("table: skinny,") and hg.plan_choice(1, 15360, 5120, tn).startswith("table: mfma,")
     near = hg.plan_choice(3000, 5120, 5120)
     assert near.startswith("neighbour: mfma,bm=256,bn=256,") and "mi=16" in near
     assert hg.plan_choice(3000, 6144, 4096).startswith("model: mfma,bm=192,bn=192,")      # 512 tiles against the neighbour's 288

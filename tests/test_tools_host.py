@@ -56,8 +56,7 @@ def test_committed_table_names_only_compiled_kernels_and_covers_the_workloads(ta
             assert "tb=1" not in spec
     for s in [wl.C1_SHAPE, *wl.C2_SHAPES, *wl.C3_SHAPES, *wl.c4_shapes(), *wl.C5_SHAPES, wl.C5_INT_SHAPE]:
         assert s in shapes, f"workload shape {s} has no table row"
-    if not table.endswith("_tn.inc"):
-        assert set(wl.C3_LARGE_SHAPES) <= shapes and set(wl.C3_OTHER_SHAPES) <= shapes
+    assert set(wl.C3_LARGE_SHAPES) <= shapes and set(wl.C3_OTHER_SHAPES) <= shapes
     # the table and the log it was written from agree
     log_shapes = {tuple(json.loads(l)["shape"]) for l in open(os.path.join(CSRC, log)) if l.strip()}
     assert log_shapes == shapes
